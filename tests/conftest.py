@@ -1,0 +1,31 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def read_golden(name):
+    """Parse tests/golden/<name>: 'key = v1 v2 ...' lines, '#' comments.
+    Repeated keys accumulate into a list of rows."""
+    out = {}
+    with open(os.path.join(ROOT, "tests", "golden", name)) as f:
+        for line in f:
+            line = line.split("#", 1)[0].strip()
+            if not line:
+                continue
+            key, vals = line.split("=", 1)
+            out.setdefault(key.strip(), []).append([float(v) for v in vals.split()])
+    return out
+
+
+@pytest.fixture(scope="session")
+def golden():
+    return read_golden
