@@ -1,0 +1,255 @@
+"""ctypes binding of libmoepp.so; same names as include/moepp.h."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_char_p, c_float, c_int32, c_size_t, c_void_p
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+F32, BF16 = 0, 1
+OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP = 0, -1, -2, -3, -4
+KERNEL_NAMES = ("router", "perm_hist", "perm_scan", "perm_scatter", "gemm1", "gemm2",
+                "combine")
+
+# every symbol include/moepp.h declares
+EXPORTS = ("moepp_workspace_bytes", "moepp_packed_bytes", "moepp_create", "moepp_destroy",
+           "moepp_pack_experts", "moepp_set_router_bias", "moepp_layer_forward",
+           "moepp_route", "moepp_permute", "moepp_expert_ffn", "moepp_combine",
+           "moepp_get_routing", "moepp_get_intermediates", "moepp_set_timing",
+           "moepp_get_timing", "moepp_set_variant", "moepp_status_str")
+
+
+class MoeppError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (what, status_str(status), status))
+
+
+class Desc(ctypes.Structure):
+    """moepp_desc"""
+    _fields_ = [(n, c_int32) for n in ("T_max", "D", "F", "n_ffn", "n_zero", "n_copy",
+                                       "n_const", "k", "act")]
+
+    @property
+    def N(self):
+        return self.n_ffn + self.n_zero + self.n_copy + self.n_const
+
+
+class _Experts(ctypes.Structure):
+    _fields_ = [("w1", c_void_p), ("w3", c_void_p), ("w2", c_void_p)]
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, "libmoepp.so")
+
+
+_lib = None
+
+
+def load_library(build_if_missing: bool = True):
+    """Load libmoepp.so.  Builds it with hipcc only when no built library is
+    present; raises if it cannot be loaded (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        if not build_if_missing:
+            raise FileNotFoundError(path)
+        from . import build as _build
+        _build.build()
+    L = ctypes.CDLL(path)
+    vp, i32, f32p = c_void_p, c_int32, c_void_p
+    L.moepp_workspace_bytes.restype = c_size_t
+    L.moepp_workspace_bytes.argtypes = [POINTER(Desc)]
+    L.moepp_packed_bytes.restype = c_size_t
+    L.moepp_packed_bytes.argtypes = [POINTER(Desc)]
+    L.moepp_create.argtypes = [POINTER(Desc), vp, c_size_t, POINTER(vp)]
+    L.moepp_destroy.argtypes = [vp]
+    L.moepp_pack_experts.argtypes = [vp, vp, POINTER(_Experts), vp, c_size_t]
+    L.moepp_set_router_bias.argtypes = [vp, f32p]
+    L.moepp_layer_forward.argtypes = [vp, vp, i32, vp, f32p, f32p, f32p, vp, vp, f32p, i32,
+                                      vp, f32p]
+    L.moepp_route.argtypes = [vp, vp, i32, vp, f32p, f32p, f32p, f32p, i32, f32p]
+    L.moepp_permute.argtypes = [vp, vp, i32, i32]
+    L.moepp_expert_ffn.argtypes = [vp, vp, i32, vp, vp, i32]
+    L.moepp_combine.argtypes = [vp, vp, i32, vp, vp, i32, vp]
+    L.moepp_get_routing.argtypes = [vp] + [POINTER(vp)] * 6
+    L.moepp_get_intermediates.argtypes = [vp] + [POINTER(vp)] * 3
+    L.moepp_set_timing.argtypes = [vp, i32]
+    L.moepp_get_timing.argtypes = [vp, POINTER(c_float)]
+    L.moepp_set_variant.argtypes = [vp, i32]
+    L.moepp_status_str.restype = c_char_p
+    L.moepp_status_str.argtypes = [i32]
+    for n in EXPORTS:
+        if n not in ("moepp_workspace_bytes", "moepp_packed_bytes", "moepp_status_str"):
+            getattr(L, n).restype = c_int32
+    _lib = L
+    return L
+
+
+def status_str(status: int) -> str:
+    return load_library().moepp_status_str(status).decode()
+
+
+def _check(status, what):
+    if status != OK:
+        raise MoeppError(status, what)
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+class Layer:
+    """One MoE++ layer context.  Tensors are torch CUDA tensors; `act` is
+    "bf16" or "f32".  Methods mirror the C entry points one to one."""
+
+    def __init__(self, T_max, D, F, n_ffn, n_zero, n_copy, n_const, k=2, act="bf16",
+                 device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.L = load_library()
+        self.desc = Desc(T_max, D, F, n_ffn, n_zero, n_copy, n_const, k,
+                         BF16 if act == "bf16" else F32)
+        self.act_dtype = torch.bfloat16 if act == "bf16" else torch.float32
+        self.device = torch.device(device)
+        nbytes = self.L.moepp_workspace_bytes(byref(self.desc))
+        if nbytes == 0:
+            probe = c_void_p()
+            st = self.L.moepp_create(byref(self.desc), c_void_p(256), 0, byref(probe))
+            raise MoeppError(st, "moepp_create")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.ctx = c_void_p()
+        _check(self.L.moepp_create(byref(self.desc), _ptr(self.workspace), nbytes,
+                                   byref(self.ctx)), "moepp_create")
+        self._bias = None
+        self.last_T = 0
+        self.last_k = k
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            self.L.moepp_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- helpers -----------------------------------------------------------
+    def _stream(self):
+        return c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _view(self, ptr, n, dtype):
+        off = ptr - self.workspace.data_ptr()
+        nb = n * self.torch.empty(0, dtype=dtype).element_size()
+        assert 0 <= off and off + nb <= self.workspace.numel()
+        return self.workspace[off:off + nb].view(dtype)
+
+    # -- C entry points ----------------------------------------------------
+    def pack_experts(self, w1, w3, w2):
+        t = self.torch
+        nbytes = self.L.moepp_packed_bytes(byref(self.desc))
+        packed = t.empty(nbytes, dtype=t.uint8, device=self.device)
+        ex = _Experts(w1.data_ptr() if w1 is not None else None,
+                      w3.data_ptr() if w3 is not None else None,
+                      w2.data_ptr() if w2 is not None else None)
+        _check(self.L.moepp_pack_experts(self.ctx, self._stream(), byref(ex), _ptr(packed),
+                                         nbytes), "moepp_pack_experts")
+        return packed
+
+    def set_router_bias(self, bias):
+        self._bias = bias          # keep the tensor alive: the library keeps the pointer
+        _check(self.L.moepp_set_router_bias(self.ctx, _ptr(bias)), "moepp_set_router_bias")
+
+    def set_variant(self, v):
+        _check(self.L.moepp_set_variant(self.ctx, v), "moepp_set_variant")
+
+    def set_timing(self, on):
+        _check(self.L.moepp_set_timing(self.ctx, 1 if on else 0), "moepp_set_timing")
+
+    def get_timing(self):
+        ms = (c_float * len(KERNEL_NAMES))()
+        _check(self.L.moepp_get_timing(self.ctx, ms), "moepp_get_timing")
+        return dict(zip(KERNEL_NAMES, [float(v) for v in ms]))
+
+    def layer_forward(self, x, prev_gate, W_g, W_res, experts, const_vecs, W_c, k=None,
+                      out=None, out_gate=None):
+        t = self.torch
+        k = self.desc.k if k is None else k
+        T = x.shape[0]
+        if out is None:
+            out = t.empty((T, self.desc.D), dtype=self.act_dtype, device=self.device)
+        if out_gate is None:
+            out_gate = t.empty((T, self.desc.N), dtype=t.float32, device=self.device)
+        _check(self.L.moepp_layer_forward(self.ctx, self._stream(), T, _ptr(x), _ptr(prev_gate),
+                                          _ptr(W_g), _ptr(W_res), _ptr(experts),
+                                          _ptr(const_vecs), _ptr(W_c), k, _ptr(out),
+                                          _ptr(out_gate)), "moepp_layer_forward")
+        self.last_T, self.last_k = T, k
+        return out, out_gate
+
+    def route(self, x, prev_gate, W_g, W_res, W_c, k=None, out_gate=None):
+        t = self.torch
+        k = self.desc.k if k is None else k
+        T = x.shape[0]
+        if out_gate is None:
+            out_gate = t.empty((T, self.desc.N), dtype=t.float32, device=self.device)
+        _check(self.L.moepp_route(self.ctx, self._stream(), T, _ptr(x), _ptr(prev_gate),
+                                  _ptr(W_g), _ptr(W_res), _ptr(W_c), k, _ptr(out_gate)),
+               "moepp_route")
+        self.last_T, self.last_k = T, k
+        return out_gate
+
+    def permute(self, T=None, k=None):
+        T = self.last_T if T is None else T
+        k = self.last_k if k is None else k
+        _check(self.L.moepp_permute(self.ctx, self._stream(), T, k), "moepp_permute")
+        self.last_T, self.last_k = T, k
+
+    def expert_ffn(self, x, experts, k=None):
+        k = self.last_k if k is None else k
+        _check(self.L.moepp_expert_ffn(self.ctx, self._stream(), x.shape[0], _ptr(x),
+                                       _ptr(experts), k), "moepp_expert_ffn")
+
+    def combine(self, x, const_vecs, k=None, out=None):
+        t = self.torch
+        k = self.last_k if k is None else k
+        if out is None:
+            out = t.empty((x.shape[0], self.desc.D), dtype=self.act_dtype, device=self.device)
+        _check(self.L.moepp_combine(self.ctx, self._stream(), x.shape[0], _ptr(x),
+                                    _ptr(const_vecs), k, _ptr(out)), "moepp_combine")
+        return out
+
+    def get_routing(self):
+        """Views into the workspace: topk_idx/topk_w [T,k], counts [N],
+        offsets [n_ffn+1], row_of/src_of [T*k]."""
+        t = self.torch
+        p = [c_void_p() for _ in range(6)]
+        _check(self.L.moepp_get_routing(self.ctx, *[byref(q) for q in p]), "moepp_get_routing")
+        T, k, d = self.last_T, self.last_k, self.desc
+        return {
+            "topk_idx": self._view(p[0].value, T * k, t.int32).view(T, k),
+            "topk_w": self._view(p[1].value, T * k, t.float32).view(T, k),
+            "counts": self._view(p[2].value, d.N, t.int32),
+            "offsets": self._view(p[3].value, d.n_ffn + 1, t.int32),
+            "row_of": self._view(p[4].value, T * k, t.int32),
+            "src_of": self._view(p[5].value, T * k, t.int32),
+        }
+
+    def get_intermediates(self, R=None):
+        """alpha1 [T,n_const]; h [R,F]; yffn [R,D] (R rows reach an FFN)."""
+        t = self.torch
+        p = [c_void_p() for _ in range(3)]
+        _check(self.L.moepp_get_intermediates(self.ctx, *[byref(q) for q in p]),
+               "moepp_get_intermediates")
+        T, d = self.last_T, self.desc
+        if R is None:
+            R = int(self.get_routing()["offsets"][-1].item()) if d.n_ffn else 0
+        out = {"alpha1": self._view(p[0].value, T * d.n_const, t.float32).view(T, d.n_const)}
+        if d.n_ffn:
+            out["h"] = self._view(p[1].value, R * d.F, self.act_dtype).view(R, d.F)
+            out["yffn"] = self._view(p[2].value, R * d.D, self.act_dtype).view(R, d.D)
+        return out

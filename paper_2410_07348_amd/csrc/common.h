@@ -1,0 +1,144 @@
+// Internal declarations shared by the HIP sources of libmoepp (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moepp {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kMaxExperts = 64;   // N
+constexpr int kMaxTopK = 8;       // K
+constexpr int kMaxConst = 8;      // constant experts
+constexpr int kWave = 64;         // CDNA wavefront
+
+// Permutation: one wave owns a chunk of kPermChunk consecutive slots.
+constexpr int kPermIters = 4;
+constexpr int kPermChunk = kWave * kPermIters;
+
+// Rows of W1 and W3 are interleaved in blocks of this many rows in the packed
+// expert buffer: [kPackBlk rows of W1][kPackBlk rows of W3] ...
+constexpr int kPackBlk = 32;
+
+// Row of the packed W1/W3 matrix [2F, D] that holds row f of W1 (up = 0) or
+// of W3 (up = 1).  The last block may be partial when F % kPackBlk != 0.
+__host__ __device__ inline int packed_row(int f, int up, int F) {
+    int b = f / kPackBlk;
+    int rem = F - b * kPackBlk;
+    int bs = rem < kPackBlk ? rem : kPackBlk;
+    return b * 2 * kPackBlk + up * bs + (f - b * kPackBlk);
+}
+
+struct Dims {
+    int T, D, F;
+    int n_ffn, n_zero, n_copy, n_const, N;
+    int k;
+};
+
+// Device pointers into the caller's workspace.
+struct Workspace {
+    int32_t *topk_idx;   // [T_max*k]
+    float *topk_w;       // [T_max*k]
+    float *alpha1;       // [T_max*n_const]
+    int32_t *counts;     // [N]
+    int32_t *offsets;    // [n_ffn+1]
+    int32_t *row_of;     // [T_max*k]
+    int32_t *src_of;     // [T_max*k]
+    int32_t *chunk_hist; // [n_chunks*N]
+    int32_t *chunk_base; // [n_chunks*N]
+    void *h;             // [T_max*k, F] act
+    void *yffn;          // [T_max*k, D] act
+};
+
+struct RouterArgs {
+    Dims d;
+    const void *x;
+    const float *prev_gate, *W_g, *W_res, *bias, *W_c;
+    float *out_gate;
+    int32_t *topk_idx;
+    float *topk_w;
+    float *alpha1;
+};
+
+struct FfnArgs {
+    Dims d;
+    const void *x;        // [T,D]
+    const void *w13;      // packed [n_ffn][2F][D]
+    const void *w2;       // [n_ffn][D][F]
+    const int32_t *offsets;
+    const int32_t *src_of;
+    void *h;              // [R,F]
+    void *yffn;           // [R,D]
+};
+
+struct CombineArgs {
+    Dims d;
+    const void *x, *const_vecs, *yffn;
+    const int32_t *topk_idx, *row_of;
+    const float *topk_w, *alpha1;
+    void *out;
+};
+
+// Launchers (each returns hipGetLastError() after its launches).
+// `bf16` selects the activation type; `which` selects GEMM1 / GEMM2.
+hipError_t launch_router_generic(const RouterArgs &a, bool bf16, hipStream_t s);
+bool router_mfma_supported(const Dims &d);
+hipError_t launch_router_mfma(const RouterArgs &a, hipStream_t s);
+
+hipError_t launch_perm_hist(const Dims &d, const Workspace &w, hipStream_t s);
+hipError_t launch_perm_scan(const Dims &d, const Workspace &w, hipStream_t s);
+hipError_t launch_perm_scatter(const Dims &d, const Workspace &w, hipStream_t s);
+
+hipError_t launch_ffn_generic(const FfnArgs &a, bool bf16, int which, hipStream_t s);
+bool ffn_mfma_supported(const Dims &d);
+hipError_t launch_ffn_mfma(const FfnArgs &a, int which, hipStream_t s);
+
+hipError_t launch_combine(const CombineArgs &a, bool bf16, hipStream_t s);
+
+hipError_t launch_pack(const Dims &d, bool bf16, const void *w1, const void *w3,
+                       const void *w2, void *w13_out, void *w2_out, hipStream_t s);
+
+// ---- small device helpers -------------------------------------------------
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+__device__ inline float to_f32(float v) { return v; }
+__device__ inline float to_f32(bf16_t v) { return (float)v; }
+
+template <typename T> struct ActVec;   // 16 bytes of activations
+template <> struct ActVec<float> {
+    static constexpr int N = 4;
+    f32x4 v;
+    __device__ float get(int i) const { return v[i]; }
+    __device__ void set(int i, float f) { v[i] = f; }
+};
+template <> struct ActVec<bf16_t> {
+    static constexpr int N = 8;
+    bf16x8 v;
+    __device__ float get(int i) const { return (float)v[i]; }
+    __device__ void set(int i, float f) { v[i] = (bf16_t)f; }
+};
+
+template <typename T>
+__device__ inline ActVec<T> load_vec(const T *p) {
+    ActVec<T> r;
+    r.v = *reinterpret_cast<const decltype(r.v) *>(p);
+    return r;
+}
+template <typename T>
+__device__ inline void store_vec(T *p, const ActVec<T> &r) {
+    *reinterpret_cast<decltype(r.v) *>(p) = r.v;
+}
+
+}  // namespace moepp

@@ -1,0 +1,458 @@
+// Host side of libmoepp: the extern "C" boundary declared in include/moepp.h.
+// Argument validation, workspace partitioning and kernel dispatch; no
+// arithmetic of the layer happens on the host.
+#include "../../include/moepp.h"
+#include "common.h"
+
+#include <new>
+
+using namespace moepp;
+
+struct moepp_ctx {
+    moepp_desc desc;
+    Workspace ws;
+    size_t ws_bytes;
+    const float *bias;
+    int variant;          // 0 auto, 1 generic, 2 require MFMA
+    int last_T, last_k;
+    bool timing;
+    bool have_events;
+    hipEvent_t ev[MOEPP_NUM_KERNELS][2];
+    bool ran[MOEPP_NUM_KERNELS];
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+int n_experts(const moepp_desc *d) { return d->n_ffn + d->n_zero + d->n_copy + d->n_const; }
+size_t elt(const moepp_desc *d) { return d->act == MOEPP_BF16 ? 2 : 4; }
+
+// 0 = ok, else the status to return
+moepp_status check_desc(const moepp_desc *d) {
+    if (!d) return MOEPP_EINVAL;
+    if (d->T_max < 1 || d->D < 1 || d->F < 1 || d->n_ffn < 0 || d->n_zero < 0 ||
+        d->n_copy < 0 || d->n_const < 0 || d->k < 1)
+        return MOEPP_EINVAL;
+    if (d->act != MOEPP_F32 && d->act != MOEPP_BF16) return MOEPP_EINVAL;
+    const long long N = (long long)d->n_ffn + d->n_zero + d->n_copy + d->n_const;
+    if (N < 1 || d->k > N) return MOEPP_EINVAL;
+    if (N > kMaxExperts || d->k > kMaxTopK || d->n_const > kMaxConst) return MOEPP_EUNSUPPORTED;
+    if (d->D % 8 != 0 || d->F % 8 != 0) return MOEPP_EUNSUPPORTED;
+    if ((long long)d->T_max * d->k >= (1ll << 30)) return MOEPP_EUNSUPPORTED;
+    return MOEPP_OK;
+}
+
+// Lays the workspace out from `base` (may be null to size it); returns bytes.
+size_t layout(const moepp_desc *d, char *base, Workspace *ws) {
+    const size_t N = n_experts(d);
+    const size_t slots = (size_t)d->T_max * d->k;
+    const size_t chunks = (slots + kPermChunk - 1) / kPermChunk;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *p = base ? base + off : nullptr;
+        off += align_up(bytes);
+        return p;
+    };
+    Workspace w;
+    w.topk_idx = (int32_t *)take(slots * 4);
+    w.topk_w = (float *)take(slots * 4);
+    w.alpha1 = (float *)take((size_t)d->T_max * (d->n_const ? d->n_const : 1) * 4);
+    w.counts = (int32_t *)take(N * 4);
+    w.offsets = (int32_t *)take(((size_t)d->n_ffn + 1) * 4);
+    w.row_of = (int32_t *)take(slots * 4);
+    w.src_of = (int32_t *)take(slots * 4);
+    w.chunk_hist = (int32_t *)take(chunks * N * 4);
+    w.chunk_base = (int32_t *)take(chunks * N * 4);
+    w.h = take(d->n_ffn ? slots * d->F * elt(d) : 0);
+    w.yffn = take(d->n_ffn ? slots * d->D * elt(d) : 0);
+    if (ws) *ws = w;
+    return off;
+}
+
+bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+Dims dims_of(const moepp_ctx *c, int T, int k) {
+    Dims d;
+    d.T = T;
+    d.D = c->desc.D;
+    d.F = c->desc.F;
+    d.n_ffn = c->desc.n_ffn;
+    d.n_zero = c->desc.n_zero;
+    d.n_copy = c->desc.n_copy;
+    d.n_const = c->desc.n_const;
+    d.N = n_experts(&c->desc);
+    d.k = k;
+    return d;
+}
+
+moepp_status check_call(const moepp_ctx *c, int T, int k) {
+    if (!c) return MOEPP_EINVAL;
+    if (T < 0 || T > c->desc.T_max) return MOEPP_EINVAL;
+    if (k < 1 || k > c->desc.k) return MOEPP_EINVAL;
+    return MOEPP_OK;
+}
+
+struct KernelTimer {
+    moepp_ctx *c;
+    hipStream_t s;
+    int which;
+    KernelTimer(moepp_ctx *c_, hipStream_t s_, int which_) : c(c_), s(s_), which(which_) {
+        if (c->timing && c->have_events) {
+            (void)hipEventRecord(c->ev[which][0], s);
+        }
+    }
+    ~KernelTimer() {
+        if (c->timing && c->have_events) {
+            (void)hipEventRecord(c->ev[which][1], s);
+            c->ran[which] = true;
+        }
+    }
+};
+
+void reset_ran(moepp_ctx *c) {
+    for (int i = 0; i < MOEPP_NUM_KERNELS; ++i) c->ran[i] = false;
+}
+
+bool use_mfma_router(const moepp_ctx *c, const Dims &d, moepp_status *st) {
+    const bool ok = c->desc.act == MOEPP_BF16 && router_mfma_supported(d);
+    if (c->variant == 2 && !ok) *st = MOEPP_EUNSUPPORTED;
+    return ok && c->variant != 1;
+}
+bool use_mfma_ffn(const moepp_ctx *c, const Dims &d, moepp_status *st) {
+    const bool ok = c->desc.act == MOEPP_BF16 && ffn_mfma_supported(d);
+    if (c->variant == 2 && !ok) *st = MOEPP_EUNSUPPORTED;
+    return ok && c->variant != 1;
+}
+
+const void *packed_w2(const moepp_ctx *c, const void *packed) {
+    const size_t w13 = (size_t)c->desc.n_ffn * 2 * c->desc.F * c->desc.D * elt(&c->desc);
+    return (const char *)packed + w13;
+}
+
+// ---- the four steps, arguments already validated ---------------------------
+moepp_status do_route(moepp_ctx *c, hipStream_t s, int T, const void *x, const float *prev_gate,
+                      const float *W_g, const float *W_res, const float *W_c, int k,
+                      float *out_gate) {
+    RouterArgs a;
+    a.d = dims_of(c, T, k);
+    a.x = x;
+    a.prev_gate = prev_gate;
+    a.W_g = W_g;
+    a.W_res = W_res;
+    a.bias = c->bias;
+    a.W_c = W_c;
+    a.out_gate = out_gate;
+    a.topk_idx = c->ws.topk_idx;
+    a.topk_w = c->ws.topk_w;
+    a.alpha1 = c->ws.alpha1;
+    moepp_status st = MOEPP_OK;
+    const bool mfma = use_mfma_router(c, a.d, &st);
+    if (st != MOEPP_OK) return st;
+    c->last_T = T;
+    c->last_k = k;
+    if (T == 0) return MOEPP_OK;
+    KernelTimer kt(c, s, MOEPP_K_ROUTER);
+    hipError_t e = mfma ? launch_router_mfma(a, s)
+                        : launch_router_generic(a, c->desc.act == MOEPP_BF16, s);
+    return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
+}
+
+moepp_status do_permute(moepp_ctx *c, hipStream_t s, int T, int k) {
+    const Dims d = dims_of(c, T, k);
+    c->last_T = T;
+    c->last_k = k;
+    hipError_t e;
+    {
+        KernelTimer kt(c, s, MOEPP_K_HIST);
+        e = launch_perm_hist(d, c->ws, s);
+    }
+    if (e != hipSuccess) return MOEPP_EHIP;
+    {
+        KernelTimer kt(c, s, MOEPP_K_SCAN);
+        e = launch_perm_scan(d, c->ws, s);
+    }
+    if (e != hipSuccess) return MOEPP_EHIP;
+    {
+        KernelTimer kt(c, s, MOEPP_K_SCATTER);
+        e = launch_perm_scatter(d, c->ws, s);
+    }
+    return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
+}
+
+moepp_status do_ffn(moepp_ctx *c, hipStream_t s, int T, const void *x, const void *experts,
+                    int k) {
+    FfnArgs a;
+    a.d = dims_of(c, T, k);
+    moepp_status st = MOEPP_OK;
+    const bool mfma = use_mfma_ffn(c, a.d, &st);
+    if (st != MOEPP_OK) return st;
+    if (T == 0 || a.d.n_ffn == 0) return MOEPP_OK;
+    a.x = x;
+    a.w13 = experts;
+    a.w2 = packed_w2(c, experts);
+    a.offsets = c->ws.offsets;
+    a.src_of = c->ws.src_of;
+    a.h = c->ws.h;
+    a.yffn = c->ws.yffn;
+    const bool bf = c->desc.act == MOEPP_BF16;
+    hipError_t e;
+    {
+        KernelTimer kt(c, s, MOEPP_K_GEMM1);
+        e = mfma ? launch_ffn_mfma(a, 0, s) : launch_ffn_generic(a, bf, 0, s);
+    }
+    if (e != hipSuccess) return MOEPP_EHIP;
+    {
+        KernelTimer kt(c, s, MOEPP_K_GEMM2);
+        e = mfma ? launch_ffn_mfma(a, 1, s) : launch_ffn_generic(a, bf, 1, s);
+    }
+    return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
+}
+
+moepp_status do_combine(moepp_ctx *c, hipStream_t s, int T, const void *x, const void *const_vecs,
+                        int k, void *out) {
+    if (T == 0) return MOEPP_OK;
+    CombineArgs a;
+    a.d = dims_of(c, T, k);
+    a.x = x;
+    a.const_vecs = const_vecs;
+    a.yffn = c->ws.yffn;
+    a.topk_idx = c->ws.topk_idx;
+    a.row_of = c->ws.row_of;
+    a.topk_w = c->ws.topk_w;
+    a.alpha1 = c->ws.alpha1;
+    a.out = out;
+    KernelTimer kt(c, s, MOEPP_K_COMBINE);
+    hipError_t e = launch_combine(a, c->desc.act == MOEPP_BF16, s);
+    return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
+}
+
+// T == 0: nothing to compute and no pointer is read
+moepp_status note_empty_call(moepp_ctx *c, int k) {
+    c->last_T = 0;
+    c->last_k = k;
+    reset_ran(c);
+    return MOEPP_OK;
+}
+
+moepp_status check_route_args(const moepp_ctx *c, const void *x, const float *prev_gate,
+                              const float *W_g, const float *W_res, const float *W_c,
+                              const float *out_gate) {
+    if (!x || !W_g || !out_gate) return MOEPP_EINVAL;
+    if ((prev_gate == nullptr) != (W_res == nullptr)) return MOEPP_EINVAL;
+    if (c->desc.n_const > 0 && !W_c) return MOEPP_EINVAL;
+    if (misaligned(x) || misaligned(W_g) || misaligned(out_gate) || misaligned(prev_gate) ||
+        misaligned(W_res) || misaligned(W_c))
+        return MOEPP_EINVAL;
+    return MOEPP_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+extern "C" {
+
+size_t moepp_workspace_bytes(const moepp_desc *desc) {
+    if (check_desc(desc) != MOEPP_OK) return 0;
+    return layout(desc, nullptr, nullptr);
+}
+
+size_t moepp_packed_bytes(const moepp_desc *desc) {
+    if (check_desc(desc) != MOEPP_OK) return 0;
+    const size_t b = (size_t)desc->n_ffn * 3 * desc->F * desc->D * elt(desc);
+    return b ? b : 16;
+}
+
+moepp_status moepp_create(const moepp_desc *desc, void *workspace, size_t bytes, moepp_ctx **ctx) {
+    if (!desc || !workspace || !ctx) return MOEPP_EINVAL;
+    moepp_status st = check_desc(desc);
+    if (st != MOEPP_OK) return st;
+    if (((uintptr_t)workspace & (kAlign - 1)) != 0) return MOEPP_EINVAL;
+    if (bytes < layout(desc, nullptr, nullptr)) return MOEPP_ENOMEM;
+    moepp_ctx *c = new (std::nothrow) moepp_ctx();
+    if (!c) return MOEPP_ENOMEM;
+    c->desc = *desc;
+    c->ws_bytes = layout(desc, (char *)workspace, &c->ws);
+    c->bias = nullptr;
+    c->variant = 0;
+    c->last_T = 0;
+    c->last_k = desc->k;
+    c->timing = false;
+    c->have_events = false;
+    reset_ran(c);
+    *ctx = c;
+    return MOEPP_OK;
+}
+
+moepp_status moepp_destroy(moepp_ctx *ctx) {
+    if (!ctx) return MOEPP_EINVAL;
+    if (ctx->have_events)
+        for (int i = 0; i < MOEPP_NUM_KERNELS; ++i) {
+            (void)hipEventDestroy(ctx->ev[i][0]);
+            (void)hipEventDestroy(ctx->ev[i][1]);
+        }
+    delete ctx;
+    return MOEPP_OK;
+}
+
+moepp_status moepp_pack_experts(moepp_ctx *ctx, void *stream, const moepp_experts *experts,
+                                void *packed, size_t bytes) {
+    if (!ctx || !packed) return MOEPP_EINVAL;
+    if (bytes < moepp_packed_bytes(&ctx->desc)) return MOEPP_ENOMEM;
+    if (ctx->desc.n_ffn == 0) return MOEPP_OK;
+    if (!experts || !experts->w1 || !experts->w3 || !experts->w2) return MOEPP_EINVAL;
+    if (misaligned(experts->w1) || misaligned(experts->w3) || misaligned(experts->w2) ||
+        misaligned(packed))
+        return MOEPP_EINVAL;
+    const Dims d = dims_of(ctx, 0, ctx->desc.k);
+    hipError_t e = launch_pack(d, ctx->desc.act == MOEPP_BF16, experts->w1, experts->w3,
+                               experts->w2, packed, const_cast<void *>(packed_w2(ctx, packed)),
+                               (hipStream_t)stream);
+    return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
+}
+
+moepp_status moepp_set_router_bias(moepp_ctx *ctx, const float *bias) {
+    if (!ctx || misaligned(bias)) return MOEPP_EINVAL;
+    ctx->bias = bias;
+    return MOEPP_OK;
+}
+
+moepp_status moepp_set_variant(moepp_ctx *ctx, int32_t variant) {
+    if (!ctx || variant < 0 || variant > 2) return MOEPP_EINVAL;
+    ctx->variant = variant;
+    return MOEPP_OK;
+}
+
+moepp_status moepp_route(moepp_ctx *ctx, void *stream, int32_t T, const void *x,
+                         const float *prev_gate, const float *W_g, const float *W_res,
+                         const float *W_c, int32_t k, float *out_gate) {
+    moepp_status st = check_call(ctx, T, k);
+    if (st != MOEPP_OK) return st;
+    if (T == 0) return note_empty_call(ctx, k);
+    st = check_route_args(ctx, x, prev_gate, W_g, W_res, W_c, out_gate);
+    if (st != MOEPP_OK) return st;
+    reset_ran(ctx);
+    return do_route(ctx, (hipStream_t)stream, T, x, prev_gate, W_g, W_res, W_c, k, out_gate);
+}
+
+moepp_status moepp_permute(moepp_ctx *ctx, void *stream, int32_t T, int32_t k) {
+    moepp_status st = check_call(ctx, T, k);
+    if (st != MOEPP_OK) return st;
+    reset_ran(ctx);
+    return do_permute(ctx, (hipStream_t)stream, T, k);
+}
+
+moepp_status moepp_expert_ffn(moepp_ctx *ctx, void *stream, int32_t T, const void *x,
+                              const void *experts, int32_t k) {
+    moepp_status st = check_call(ctx, T, k);
+    if (st != MOEPP_OK) return st;
+    if (T == 0) return note_empty_call(ctx, k);
+    if (!x || misaligned(x)) return MOEPP_EINVAL;
+    if (ctx->desc.n_ffn > 0 && (!experts || misaligned(experts))) return MOEPP_EINVAL;
+    reset_ran(ctx);
+    return do_ffn(ctx, (hipStream_t)stream, T, x, experts, k);
+}
+
+moepp_status moepp_combine(moepp_ctx *ctx, void *stream, int32_t T, const void *x,
+                           const void *const_vecs, int32_t k, void *out) {
+    moepp_status st = check_call(ctx, T, k);
+    if (st != MOEPP_OK) return st;
+    if (T == 0) return note_empty_call(ctx, k);
+    if (!x || !out || misaligned(x) || misaligned(out)) return MOEPP_EINVAL;
+    if (ctx->desc.n_const > 0 && (!const_vecs || misaligned(const_vecs))) return MOEPP_EINVAL;
+    reset_ran(ctx);
+    return do_combine(ctx, (hipStream_t)stream, T, x, const_vecs, k, out);
+}
+
+moepp_status moepp_layer_forward(moepp_ctx *ctx, void *stream, int32_t T, const void *x,
+                                 const float *prev_gate, const float *W_g, const float *W_res,
+                                 const void *experts, const void *const_vecs, const float *W_c,
+                                 int32_t k, void *out, float *out_gate) {
+    moepp_status st = check_call(ctx, T, k);
+    if (st != MOEPP_OK) return st;
+    if (T == 0) return note_empty_call(ctx, k);
+    st = check_route_args(ctx, x, prev_gate, W_g, W_res, W_c, out_gate);
+    if (st != MOEPP_OK) return st;
+    if (!out || misaligned(out)) return MOEPP_EINVAL;
+    if (ctx->desc.n_ffn > 0 && (!experts || misaligned(experts))) return MOEPP_EINVAL;
+    if (ctx->desc.n_const > 0 && (!const_vecs || misaligned(const_vecs))) return MOEPP_EINVAL;
+    // variant 2 must fail before anything is launched
+    {
+        const Dims d = dims_of(ctx, T, k);
+        moepp_status s2 = MOEPP_OK;
+        (void)use_mfma_router(ctx, d, &s2);
+        (void)use_mfma_ffn(ctx, d, &s2);
+        if (s2 != MOEPP_OK) return s2;
+    }
+    reset_ran(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    st = do_route(ctx, s, T, x, prev_gate, W_g, W_res, W_c, k, out_gate);
+    if (st != MOEPP_OK) return st;
+    st = do_permute(ctx, s, T, k);
+    if (st != MOEPP_OK) return st;
+    st = do_ffn(ctx, s, T, x, experts, k);
+    if (st != MOEPP_OK) return st;
+    return do_combine(ctx, s, T, x, const_vecs, k, out);
+}
+
+moepp_status moepp_get_routing(moepp_ctx *ctx, const int32_t **topk_idx, const float **topk_w,
+                               const int32_t **counts, const int32_t **offsets,
+                               const int32_t **row_of, const int32_t **src_of) {
+    if (!ctx) return MOEPP_EINVAL;
+    if (topk_idx) *topk_idx = ctx->ws.topk_idx;
+    if (topk_w) *topk_w = ctx->ws.topk_w;
+    if (counts) *counts = ctx->ws.counts;
+    if (offsets) *offsets = ctx->ws.offsets;
+    if (row_of) *row_of = ctx->ws.row_of;
+    if (src_of) *src_of = ctx->ws.src_of;
+    return MOEPP_OK;
+}
+
+moepp_status moepp_get_intermediates(moepp_ctx *ctx, const float **alpha1, const void **h,
+                                     const void **yffn) {
+    if (!ctx) return MOEPP_EINVAL;
+    if (alpha1) *alpha1 = ctx->ws.alpha1;
+    if (h) *h = ctx->ws.h;
+    if (yffn) *yffn = ctx->ws.yffn;
+    return MOEPP_OK;
+}
+
+moepp_status moepp_set_timing(moepp_ctx *ctx, int32_t enable) {
+    if (!ctx) return MOEPP_EINVAL;
+    if (enable && !ctx->have_events) {
+        for (int i = 0; i < MOEPP_NUM_KERNELS; ++i)
+            for (int j = 0; j < 2; ++j)
+                if (hipEventCreate(&ctx->ev[i][j]) != hipSuccess) return MOEPP_EHIP;
+        ctx->have_events = true;
+    }
+    ctx->timing = enable != 0;
+    reset_ran(ctx);
+    return MOEPP_OK;
+}
+
+moepp_status moepp_get_timing(moepp_ctx *ctx, float *ms) {
+    if (!ctx || !ms) return MOEPP_EINVAL;
+    for (int i = 0; i < MOEPP_NUM_KERNELS; ++i) {
+        ms[i] = 0.f;
+        if (ctx->have_events && ctx->ran[i]) {
+            if (hipEventSynchronize(ctx->ev[i][1]) != hipSuccess) return MOEPP_EHIP;
+            if (hipEventElapsedTime(&ms[i], ctx->ev[i][0], ctx->ev[i][1]) != hipSuccess)
+                return MOEPP_EHIP;
+        }
+    }
+    return MOEPP_OK;
+}
+
+const char *moepp_status_str(moepp_status status) {
+    switch (status) {
+        case MOEPP_OK: return "ok";
+        case MOEPP_EINVAL: return "invalid argument";
+        case MOEPP_EUNSUPPORTED: return "unsupported configuration";
+        case MOEPP_ENOMEM: return "buffer too small";
+        case MOEPP_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

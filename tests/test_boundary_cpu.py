@@ -1,0 +1,182 @@
+"""Host-side tests of the C ABI that need no GPU: the library loads, exports
+every symbol include/moepp.h declares, sizes its buffers sensibly and rejects
+bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+from ctypes import byref, c_void_p
+
+import pytest
+
+import paper_2410_07348_amd as M
+from paper_2410_07348_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    return M.load_library()
+
+
+def desc(**kw):
+    d = dict(T_max=128, D=64, F=96, n_ffn=4, n_zero=1, n_copy=1, n_const=2, k=2, act=B.BF16)
+    d.update(kw)
+    return M.Desc(*[d[n] for n, _ in M.Desc._fields_])
+
+
+def fake(addr=0x10000):
+    """A well-aligned non-null 'device pointer' for calls that must fail
+    during validation, before any kernel could read it."""
+    return c_void_p(addr)
+
+
+def test_library_exports_every_declared_symbol(L):
+    hdr = open(os.path.join(ROOT, "include", "moepp.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(moepp_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(M.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings(L):
+    for st in (0, -1, -2, -3, -4):
+        assert L.moepp_status_str(st)
+    assert L.moepp_status_str(-99) == b"unknown status"
+
+
+def test_workspace_and_packed_sizes(L):
+    d = desc()
+    ws = L.moepp_workspace_bytes(byref(d))
+    slots = d.T_max * d.k
+    # must at least hold h [slots,F] and yffn [slots,D] in bf16 plus the index arrays
+    assert ws >= slots * (d.F + d.D) * 2 + 4 * slots * 4
+    assert ws % 256 == 0
+    assert L.moepp_packed_bytes(byref(d)) == d.n_ffn * 3 * d.F * d.D * 2
+    d32 = desc(act=B.F32)
+    assert L.moepp_packed_bytes(byref(d32)) == d.n_ffn * 3 * d.F * d.D * 4
+    assert L.moepp_workspace_bytes(byref(d32)) > ws
+    # grows with T_max
+    assert L.moepp_workspace_bytes(byref(desc(T_max=256))) > ws
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(T_max=0), B.EINVAL), (dict(D=0), B.EINVAL), (dict(k=0), B.EINVAL),
+    (dict(k=9, n_ffn=20), B.EUNSUPPORTED), (dict(k=5, n_ffn=1, n_zero=1, n_copy=1, n_const=1), B.EINVAL),
+    (dict(n_ffn=-1), B.EINVAL), (dict(act=7), B.EINVAL),
+    (dict(n_ffn=61), B.EUNSUPPORTED), (dict(n_const=9), B.EUNSUPPORTED),
+    (dict(D=60), B.EUNSUPPORTED), (dict(F=100), B.EUNSUPPORTED),
+    (dict(T_max=1 << 30), B.EUNSUPPORTED),
+    (dict(n_ffn=0, n_zero=0, n_copy=0, n_const=0), B.EINVAL),
+])
+def test_invalid_descriptors(L, kw, status):
+    d = desc(**kw)
+    assert L.moepp_workspace_bytes(byref(d)) == 0
+    assert L.moepp_packed_bytes(byref(d)) == 0
+    ctx = c_void_p()
+    assert L.moepp_create(byref(d), fake(), 1 << 40, byref(ctx)) == status
+    assert not ctx.value
+
+
+def test_create_argument_checks(L):
+    d = desc()
+    need = L.moepp_workspace_bytes(byref(d))
+    ctx = c_void_p()
+    assert L.moepp_create(None, fake(), need, byref(ctx)) == B.EINVAL
+    assert L.moepp_create(byref(d), None, need, byref(ctx)) == B.EINVAL
+    assert L.moepp_create(byref(d), fake(), need, None) == B.EINVAL
+    assert L.moepp_create(byref(d), fake(0x10010), need, byref(ctx)) == B.EINVAL   # misaligned
+    assert L.moepp_create(byref(d), fake(), need - 1, byref(ctx)) == B.ENOMEM
+    assert L.moepp_create(byref(d), fake(), need, byref(ctx)) == B.OK
+    assert ctx.value
+    assert L.moepp_destroy(ctx) == B.OK
+    assert L.moepp_destroy(None) == B.EINVAL
+
+
+@pytest.fixture()
+def ctx(L):
+    d = desc()
+    c = c_void_p()
+    assert L.moepp_create(byref(d), fake(), L.moepp_workspace_bytes(byref(d)), byref(c)) == B.OK
+    yield c
+    L.moepp_destroy(c)
+
+
+def fwd(L, ctx, **kw):
+    a = dict(stream=None, T=16, x=fake(), prev_gate=fake(), W_g=fake(), W_res=fake(),
+             experts=fake(), const_vecs=fake(), W_c=fake(), k=2, out=fake(), out_gate=fake())
+    a.update(kw)
+    return L.moepp_layer_forward(ctx, a["stream"], a["T"], a["x"], a["prev_gate"], a["W_g"],
+                                 a["W_res"], a["experts"], a["const_vecs"], a["W_c"], a["k"],
+                                 a["out"], a["out_gate"])
+
+
+def test_forward_rejects_bad_arguments_before_launching(L, ctx):
+    assert fwd(L, None) == B.EINVAL
+    assert fwd(L, ctx, T=-1) == B.EINVAL
+    assert fwd(L, ctx, T=129) == B.EINVAL                 # > T_max
+    assert fwd(L, ctx, k=0) == B.EINVAL
+    assert fwd(L, ctx, k=3) == B.EINVAL                   # > desc.k
+    for name in ("x", "W_g", "out", "out_gate", "experts", "const_vecs", "W_c"):
+        assert fwd(L, ctx, **{name: None}) == B.EINVAL, name
+        assert fwd(L, ctx, **{name: fake(0x10004)}) == B.EINVAL, name    # misaligned
+    assert fwd(L, ctx, prev_gate=None) == B.EINVAL        # W_res without prev_gate
+    assert fwd(L, ctx, W_res=None) == B.EINVAL
+
+
+def test_step_calls_reject_bad_arguments(L, ctx):
+    assert L.moepp_route(ctx, None, 16, None, None, fake(), None, fake(), 2, fake()) == B.EINVAL
+    assert L.moepp_route(ctx, None, 16, fake(), fake(), fake(), None, fake(), 2, fake()) == B.EINVAL
+    assert L.moepp_permute(ctx, None, 1000, 2) == B.EINVAL
+    assert L.moepp_permute(None, None, 1, 2) == B.EINVAL
+    assert L.moepp_expert_ffn(ctx, None, 16, None, fake(), 2) == B.EINVAL
+    assert L.moepp_expert_ffn(ctx, None, 16, fake(), None, 2) == B.EINVAL
+    assert L.moepp_combine(ctx, None, 16, fake(), fake(), 2, None) == B.EINVAL
+    assert L.moepp_combine(ctx, None, 16, fake(), None, 2, fake()) == B.EINVAL
+    assert L.moepp_set_variant(ctx, 3) == B.EINVAL
+    assert L.moepp_set_variant(ctx, 1) == B.OK
+    assert L.moepp_set_router_bias(ctx, fake(0x10004)) == B.EINVAL
+    assert L.moepp_set_router_bias(ctx, None) == B.OK
+    assert L.moepp_get_timing(ctx, None) == B.EINVAL
+
+
+def test_pack_argument_checks(L, ctx):
+    d = desc()
+    need = L.moepp_packed_bytes(byref(d))
+    ex = B._Experts(0x10000, 0x20000, 0x30000)
+    assert L.moepp_pack_experts(ctx, None, byref(ex), fake(), need - 1) == B.ENOMEM
+    assert L.moepp_pack_experts(ctx, None, None, fake(), need) == B.EINVAL
+    assert L.moepp_pack_experts(ctx, None, byref(B._Experts(0x10000, None, 0x30000)), fake(),
+                                need) == B.EINVAL
+    assert L.moepp_pack_experts(ctx, None, byref(ex), None, need) == B.EINVAL
+
+
+def test_mfma_variant_is_refused_for_fp32_layers(L):
+    d = desc(act=B.F32)
+    c = c_void_p()
+    assert L.moepp_create(byref(d), fake(), L.moepp_workspace_bytes(byref(d)), byref(c)) == B.OK
+    assert L.moepp_set_variant(c, 2) == B.OK
+    assert fwd(L, c) == B.EUNSUPPORTED
+    L.moepp_destroy(c)
+
+
+def test_get_routing_points_into_the_workspace(L, ctx):
+    p = [c_void_p() for _ in range(6)]
+    assert L.moepp_get_routing(ctx, *[byref(q) for q in p]) == B.OK
+    d = desc()
+    ws = L.moepp_workspace_bytes(byref(d))
+    vals = [q.value for q in p]
+    assert len(set(vals)) == 6
+    assert all(0x10000 <= v < 0x10000 + ws and v % 256 == 0 for v in vals)
+    q = [c_void_p() for _ in range(3)]
+    assert L.moepp_get_intermediates(ctx, *[byref(v) for v in q]) == B.OK
+    assert all(0x10000 <= v.value < 0x10000 + ws for v in q)
+    assert L.moepp_get_routing(ctx, None, None, None, None, None, None) == B.OK
+
+
+def test_binding_has_no_cpu_fallback():
+    src = open(os.path.join(ROOT, "paper_2410_07348_amd", "binding.py")).read()
+    assert "oracle" not in src
+    with pytest.raises((FileNotFoundError, OSError)):
+        ctypes.CDLL(os.path.join(ROOT, "paper_2410_07348_amd", "no_such_lib.so"))

@@ -1,0 +1,254 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by
+element, on seeded inputs.  Needs a real MI355X: run with -m gpu."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import WORKLOADS, LayerShape, make_inputs
+
+from helpers import (check_layer, gpu_forward, make_layer, sample_tokens, to_device, rel_err,
+                     TOL_OUT)
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def small_shape(name, **kw):
+    base = dict(T=300, D=256, F=384, n_ffn=5, n_zero=1, n_copy=1, n_const=2, k=2,
+                act="bf16", seed=77)
+    base.update(kw)
+    return LayerShape(name, **base)
+
+
+def forced_routing(shape, idx, seed=5):
+    """Inputs whose routing is dictated: W = 0 and W_g (residual) = I, so
+    G(x) = G(x_prev) exactly (Eq.6) and prev_gate decides the Top-K."""
+    inp = make_inputs(shape.with_(residual=True, bias="none"))
+    N = shape.N
+    rng = np.random.default_rng(seed)
+    pg = (-10.0 + rng.random((shape.T, N))).astype(np.float32)
+    for s in range(shape.k):
+        pg[np.arange(shape.T), idx[:, s]] = 10.0 - s
+    inp["prev_gate"] = pg
+    inp["W_g"] = np.zeros((N, shape.D), np.float32)
+    inp["W_res"] = np.eye(N, dtype=np.float32)
+    inp["bias"] = None
+    return inp
+
+
+# ----------------------------------------------------------------- small cases
+def test_tiny_fp32_workload_all_tokens():
+    s = WORKLOADS["tiny"]
+    inp = make_inputs(s)
+    say("case tiny fp32", s)
+    res = gpu_forward(s, inp)
+    errs = check_layer(s, inp, res)
+    say("tiny errs", errs)
+    assert set(np.unique(res["topk_idx"])) == set(range(s.N))
+
+
+@pytest.mark.parametrize("variant", [1, 0])
+@pytest.mark.parametrize("kw", [
+    dict(),                                            # several tiles + ragged tail
+    dict(T=1000, D=512, F=640, n_ffn=7, seed=78),
+    dict(T=257, D=128, F=64, n_ffn=3, n_const=1, seed=79),
+    dict(T=129, D=192, F=320, n_ffn=6, n_const=3, k=3, seed=80),   # D, F not multiples of 128
+    dict(T=64, D=64, F=64, n_ffn=2, n_zero=0, n_copy=0, n_const=0, k=1, seed=81),
+    dict(T=2000, D=256, F=256, n_ffn=20, n_zero=0, n_copy=0, n_const=0, seed=82),  # vanilla
+    dict(T=500, D=256, F=128, n_ffn=4, n_zero=2, n_copy=2, n_const=4, k=4, seed=83),
+    dict(T=333, D=256, F=384, residual=False, seed=84),             # first layer, Eq.6 j = 1
+    dict(T=333, D=256, F=384, bias="normal", seed=85),
+    dict(T=96, D=1024, F=2048, n_ffn=8, seed=86),
+])
+def test_bf16_layers_all_tokens(kw, variant):
+    s = small_shape("case", **kw)
+    inp = make_inputs(s)
+    say("case", kw, "variant", variant)
+    res = gpu_forward(s, inp, variant=variant)
+    say("errs", check_layer(s, inp, res))
+
+
+@pytest.mark.parametrize("kw", [
+    dict(T=200, D=64, F=96, seed=90),
+    dict(T=50, D=8, F=8, n_ffn=2, n_const=1, seed=91),             # smallest legal D, F
+    dict(T=130, D=72, F=40, n_ffn=3, k=3, seed=92),                # F % 32 != 0 (partial pack block)
+])
+def test_fp32_layers_all_tokens(kw):
+    s = small_shape("case32", act="f32", **kw)
+    inp = make_inputs(s)
+    say("case fp32", kw)
+    res = gpu_forward(s, inp)
+    say("errs", check_layer(s, inp, res))
+
+
+# ------------------------------------------------------------------ edge cases
+@pytest.mark.parametrize("variant", [1, 0])
+def test_edge_routing_patterns(variant):
+    s = small_shape("edge", T=700, n_ffn=6)
+    N, nf = s.N, s.n_ffn
+    rng = np.random.default_rng(3)
+    zc = np.arange(nf, N)
+    patterns = {}
+    # every slot on a zero-computation expert: R = 0, the GEMMs have nothing to do
+    patterns["all_zc"] = np.stack([rng.permutation(zc)[:2] for _ in range(s.T)])
+    # every slot on an FFN expert
+    patterns["all_ffn"] = np.stack([rng.permutation(nf)[:2] for _ in range(s.T)])
+    # expert 2 empty, expert 4 has exactly one row, expert 0 takes most tokens
+    idx = np.stack([rng.permutation([0, 1, 3, 5] + zc.tolist())[:2] for _ in range(s.T)])
+    idx[:, 0] = np.where(rng.random(s.T) < 0.7, 0, idx[:, 0])
+    idx[:, 1] = np.where(idx[:, 1] == idx[:, 0], 1, idx[:, 1])
+    idx[17] = [4, 0]
+    patterns["empty_and_single"] = idx
+    # zero + copy for every token: the layer is bypassed up to the gate weight
+    patterns["zero_copy"] = np.tile(np.array([[nf + 1, nf]]), (s.T, 1))
+    # one expert holds everything (one long group), second slot constant experts
+    patterns["one_group"] = np.stack([np.full(s.T, 3), nf + 2 + (np.arange(s.T) % 2)], 1)
+    for name, idx in patterns.items():
+        say("edge pattern", name, "variant", variant)
+        inp = forced_routing(s, idx.astype(np.int64))
+        res = gpu_forward(s, inp, variant=variant)
+        assert np.array_equal(res["topk_idx"], idx), name
+        errs = check_layer(s, inp, res, max_near_ties=0)
+        say(name, errs)
+        if name == "all_zc":
+            assert errs["R"] == 0
+        if name == "empty_and_single":
+            assert res["counts"][2] == 0 and res["counts"][4] == 1
+        if name == "zero_copy":
+            g = res["topk_w"][:, 0].astype(np.float64)
+            assert rel_err(res["out"], g[:, None] * inp["x"]) <= TOL_OUT["bf16"]
+
+
+@pytest.mark.parametrize("kw", [dict(T=1), dict(T=2, k=1), dict(T=63), dict(T=65),
+                                dict(T=5, n_ffn=2, n_zero=1, n_copy=1, n_const=0, k=4)])
+def test_tiny_token_counts(kw):
+    s = small_shape("few", **kw)
+    inp = make_inputs(s)
+    say("few tokens", kw)
+    for variant in (1, 0):
+        res = gpu_forward(s, inp, variant=variant)
+        check_layer(s, inp, res)
+
+
+def test_zero_tokens_and_smaller_T_than_T_max():
+    s = small_shape("tmax", T=200)
+    inp = make_inputs(s)
+    dev = to_device(s, inp)
+    L = make_layer(s, T_max=512)
+    res = gpu_forward(s, inp, layer=L, dev=dev)
+    check_layer(s, inp, res)
+    s0 = s.with_(T=0)
+    res0 = gpu_forward(s0, inp, layer=L, dev=dev)
+    assert res0["out"].shape == (0, s.D)
+    # a shorter call on the same context afterwards
+    s2 = s.with_(T=77)
+    inp2 = {k: (v[:77] if k in ("x", "prev_gate") else v) for k, v in inp.items()}
+    res2 = gpu_forward(s2, inp2, layer=L, dev=dev)
+    check_layer(s2, inp2, res2)
+
+
+def test_no_ffn_experts_layer():
+    s = small_shape("zc_only", n_ffn=0, n_zero=1, n_copy=2, n_const=2, T=150)
+    inp = make_inputs(s)
+    res = gpu_forward(s, inp)
+    check_layer(s, inp, res)
+
+
+def test_two_runs_are_bytewise_identical():
+    import torch
+    s = small_shape("determinism", T=1500, D=512, F=384)
+    inp = make_inputs(s)
+    dev = to_device(s, inp)
+    L = make_layer(s)
+    packed = L.pack_experts(dev["w1"], dev["w3"], dev["w2"])
+    outs = []
+    for _ in range(2):
+        out, gate = L.layer_forward(dev["x"], dev["prev_gate"], dev["W_g"], dev["W_res"], packed,
+                                    dev["const_vecs"], dev["W_c"])
+        torch.cuda.synchronize()
+        r = L.get_routing()
+        outs.append([out.clone(), gate.clone()] + [r[k].clone() for k in sorted(r)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_step_calls_equal_the_fused_call_and_timing_reports():
+    import torch
+    s = small_shape("steps", T=640, D=256, F=256)
+    inp = make_inputs(s)
+    dev = to_device(s, inp)
+    L = make_layer(s)
+    packed = L.pack_experts(dev["w1"], dev["w3"], dev["w2"])
+    out, gate = L.layer_forward(dev["x"], dev["prev_gate"], dev["W_g"], dev["W_res"], packed,
+                                dev["const_vecs"], dev["W_c"])
+    torch.cuda.synchronize()
+    out = out.clone()
+    L.set_timing(True)
+    gate2 = L.route(dev["x"], dev["prev_gate"], dev["W_g"], dev["W_res"], dev["W_c"])
+    L.permute()
+    L.expert_ffn(dev["x"], packed)
+    out2 = L.combine(dev["x"], dev["const_vecs"])
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) and torch.equal(gate, gate2)
+    L.layer_forward(dev["x"], dev["prev_gate"], dev["W_g"], dev["W_res"], packed,
+                    dev["const_vecs"], dev["W_c"])
+    ms = L.get_timing()
+    say("kernel ms", ms)
+    assert all(v > 0 for v in ms.values())
+    L.set_timing(False)
+
+
+def test_mfma_and_generic_kernels_agree():
+    """The two kernel families must give the same routing and close outputs."""
+    s = small_shape("families", T=900, D=512, F=768, n_ffn=6)
+    inp = make_inputs(s)
+    a = gpu_forward(s, inp, variant=1)
+    b = gpu_forward(s, inp, variant=2)
+    assert rel_err(b["out_gate"], a["out_gate"]) <= 1e-5
+    same = (a["topk_idx"] == b["topk_idx"]).all(axis=1)
+    assert same.mean() > 0.995
+    assert rel_err(b["out"][same], a["out"][same]) <= 1e-2
+
+
+# ------------------------------------------------- the benchmark's own shapes
+def _full_size(name, n_sample, check_inter=True):
+    s = WORKLOADS[name]
+    say("workload", name, s)
+    inp = make_inputs(s)
+    say("inputs ready")
+    res = gpu_forward(s, inp, variant=0)
+    say("gpu done, R =", int(res["offsets"][-1]), "counts", res["counts"].tolist())
+    toks = None if n_sample is None else sample_tokens(s, res["topk_idx"], n_sample, seed=s.seed)
+    errs = check_layer(s, inp, res, tok_list=toks, check_inter=check_inter)
+    say(name, "errs", errs)
+    return s, res, errs
+
+
+def test_workload_small_all_tokens():
+    s, res, errs = _full_size("small", None, check_inter=False)
+    assert abs(errs["R"] / (s.T * s.k) - s.n_ffn / s.N) < 0.01      # Tab.1 with tau = 1
+
+
+def test_workload_mid_ragged_groups_sampled():
+    s, res, errs = _full_size("mid", 768)
+    c = res["counts"][:s.n_ffn]
+    assert c.max() > 8 * max(c.min(), 1)
+
+
+def test_workload_skew_sampled():
+    s, res, errs = _full_size("skew", 768)
+    c = res["counts"].astype(np.float64)
+    assert abs(c[s.n_ffn:].sum() / c.sum() - 0.5) < 0.03
+    assert abs(c[0] / c[1:s.n_ffn].mean() - 4.0) < 0.5
+
+
+def test_workload_smallbatch_all_tokens():
+    _full_size("smallbatch", None)
+
+
+def test_workload_large_sampled():
+    s, res, errs = _full_size("large", 384)
+    assert abs(errs["R"] / (s.T * s.k) - s.n_ffn / s.N) < 0.01
