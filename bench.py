@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE++ layer forward on one MI355X.
+
+One "step" is one pass of the whole hot path (router + gating residual,
+softmax/top-k, permutation, grouped SwiGLU FFN, combine with the
+zero-computation experts) over one batch of seeded synthetic tokens that is
+already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large]
+
+The default workload is the large bf16 layer (T = 8 x 4096 tokens, D = 4096,
+F = 5632, 16 FFN + 1 zero + 1 copy + 2 constant experts, top-2), the one the
+roofline targets are quoted on.  The same shape with the zero-computation
+experts disabled (vanilla MoE, 20 and 16 FFN experts) is timed right after it
+for the throughput ratio, and the CPU oracle is timed on a bounded sample of
+the same tokens as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+import numpy as np
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16, published
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def run_gpu(shape, inp, steps, warmup):
+    """Timed steps of moepp_layer_forward on cuda:0.  Returns a dict."""
+    import torch
+    from helpers import make_layer, to_device
+    dev = to_device(shape, inp)
+    L = make_layer(shape)
+    packed = L.pack_experts(dev["w1"], dev["w3"], dev["w2"]) if shape.n_ffn else None
+    for k in ("w1", "w3", "w2"):          # only the packed copy is needed from here on
+        dev[k] = None
+    L.set_router_bias(dev.get("bias"))
+    cv = dev["const_vecs"] if shape.n_const else None
+    wc = dev["W_c"] if shape.n_const else None
+    out = torch.empty((shape.T, shape.D), dtype=L.act_dtype, device=L.device)
+    out_gate = torch.empty((shape.T, shape.N), dtype=torch.float32, device=L.device)
+
+    def step():
+        L.layer_forward(dev["x"], dev.get("prev_gate"), dev["W_g"], dev.get("W_res"), packed, cv,
+                        wc, k=shape.k, out=out, out_gate=out_gate)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    L.set_timing(True)                    # HIP events around every kernel, on the launch stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern = L.get_timing()                 # per-kernel average over the timed steps (last 64)
+    L.set_timing(False)
+    r = L.get_routing()
+    counts = r["counts"].cpu().numpy().copy()
+    R = int(r["offsets"][-1].item()) if shape.n_ffn else 0
+    res = {"ms_per_step": wall / steps * 1e3, "kernel_ms": kern, "R": R,
+           "counts": counts.tolist(),
+           "topk_idx": r["topk_idx"].cpu().numpy().copy(),
+           "out": out, "layer": L, "dev": dev}
+    return res
+
+
+def roofline_numbers(shape, g):
+    """Algorithmic work per launch / measured duration, per kernel."""
+    T, D, F, N, K, R = shape.T, shape.D, shape.F, shape.N, shape.k, g["R"]
+    b = 2 if shape.act == "bf16" else 4
+    km = g["kernel_ms"]
+    out = {}
+    if km["gemm1"] > 0:
+        fl1, fl2 = 4.0 * D * F * R, 2.0 * D * F * R
+        out["gemm1_tflops"] = fl1 / (km["gemm1"] * 1e-3) / 1e12
+        out["gemm2_tflops"] = fl2 / (km["gemm2"] * 1e-3) / 1e12
+        out["ffn_tflops"] = (fl1 + fl2) / ((km["gemm1"] + km["gemm2"]) * 1e-3) / 1e12
+    router_bytes = T * (D * b + (N * 4 if shape.residual else 0) + N * 4 + K * 8 + shape.n_const * 4)
+    out["router_gbs"] = router_bytes / (km["router"] * 1e-3) / 1e9
+    combine_bytes = (R + 2 * T) * D * b
+    out["combine_gbs"] = combine_bytes / (km["combine"] * 1e-3) / 1e9
+    out["permute_us"] = (km["perm_hist"] + km["perm_scan"] + km["perm_scatter"]) * 1e3
+    return out
+
+
+def cpu_baseline(shape, inp, target_s=15.0):
+    """The CPU oracle timed on a bounded sample of the workload's tokens."""
+    import oracle
+
+    def timed(n):
+        toks = np.arange(n, dtype=np.int32)          # the first n tokens of the seeded batch
+        sub = shape.with_(T=n)
+        t0 = time.perf_counter()
+        r = oracle.route(sub, inp["x"][:n], None if inp["prev_gate"] is None else inp["prev_gate"][:n],
+                         inp["W_g"], inp["W_res"], inp["bias"])
+        oracle.permute(sub, r["topk_idx"])
+        oracle.experts(sub, inp["x"][:n], r["topk_idx"], r["topk_w"], inp["w1"], inp["w3"],
+                       inp["w2"], inp["const_vecs"], inp["W_c"], tok_list=toks)
+        return time.perf_counter() - t0
+
+    cores = oracle.threads()
+    n0 = min(shape.T, max(cores * 2, 32))
+    t_probe = timed(n0)
+    n = int(min(shape.T, max(n0, n0 * target_s / max(t_probe, 1e-3))))
+    n = max(cores, n // cores * cores)
+    t = timed(n) if n > n0 else t_probe
+    return {"value": n / t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d of %d tokens of the same seeded batch, full layer "
+                      "(route + permute + experts), %.1f s wall" % (n, shape.T, t)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="large")
+    ap.add_argument("--no-vanilla", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs the layer on one GPU only; --gpus %d is not "
+                 "supported (sharding is described in DESIGN.md)" % args.gpus)
+
+    import torch
+    from workloads import WORKLOADS, make_inputs, ffn_work_fraction
+    import paper_2410_07348_amd as M
+    M.load_library()
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    shape = WORKLOADS[args.workload]
+    log("generating", shape)
+    inp = make_inputs(shape)
+    g = run_gpu(shape, inp, args.steps, args.warmup)
+    rf = roofline_numbers(shape, g)
+    log("moe++  ms/step %.3f" % g["ms_per_step"], g["kernel_ms"], rf)
+    km = g["kernel_ms"]
+    expert_ms = km["gemm1"] + km["gemm2"] + km["combine"]
+
+    result = {
+        "metric": "moepp_layer_forward_tokens_per_s",
+        "value": shape.T / (g["ms_per_step"] * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": g["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.act == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": shape.name, "T": shape.T, "D": shape.D, "F": shape.F,
+                   "n_ffn": shape.n_ffn, "n_zero": shape.n_zero, "n_copy": shape.n_copy,
+                   "n_const": shape.n_const, "top_k": shape.k, "bias": shape.bias,
+                   "gating_residual": shape.residual, "ffn_rows_R": g["R"],
+                   "weights": "packed once before timing"},
+        "kernel_ms": km,
+        "expert_forward_tokens_per_s": shape.T / (expert_ms * 1e-3) if expert_ms > 0 else None,
+        "pct_bf16_mfma_peak_ffn": 100.0 * rf.get("ffn_tflops", 0.0) / PEAK_BF16_MFMA_TFLOPS,
+        "router_gbs": rf["router_gbs"], "combine_gbs": rf["combine_gbs"],
+        "permute_us": rf["permute_us"],
+        "gemm2_tflops": rf.get("gemm2_tflops"),
+    }
+    if "gemm1_tflops" in rf:
+        result["roofline"] = {"kernel": "k_grouped_gemm<SwiGLU> (GEMM1: W1/W3 + SwiGLU)",
+                              "bound": "mfma", "achieved": rf["gemm1_tflops"],
+                              "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                              "frac": rf["gemm1_tflops"] / PEAK_BF16_MFMA_TFLOPS,
+                              "traffic": None}
+    else:
+        result["roofline"] = {"kernel": "k_combine", "bound": "hbm",
+                              "achieved": rf["combine_gbs"], "peak": PEAK_HBM_GBS,
+                              "unit": "GB/s", "frac": rf["combine_gbs"] / PEAK_HBM_GBS,
+                              "traffic": None}
+
+    # ---- vanilla MoE: same T/D/F/k, zero-computation experts disabled --------
+    if not args.no_vanilla and shape.n_zc > 0 and shape.name == "large":
+        del g["layer"], g["dev"], g["out"]
+        torch.cuda.empty_cache()
+        van = {}
+        for vname in ("large_vanilla16", "large_vanilla20"):
+            vs = WORKLOADS[vname]
+            log("generating", vs.name)
+            if vs.n_ffn == shape.n_ffn:
+                # same seed -> the same expert weights; only the router side differs
+                vin = dict(make_inputs(vs.with_(F=8)), w1=inp["w1"], w3=inp["w3"], w2=inp["w2"])
+            else:
+                vin = make_inputs(vs)
+            gv = run_gpu(vs, vin, args.steps, args.warmup)
+            kv = gv["kernel_ms"]
+            van[vname] = {"ms_per_step": gv["ms_per_step"], "R": gv["R"], "kernel_ms": kv,
+                          "tokens_per_s": vs.T / (gv["ms_per_step"] * 1e-3),
+                          "ratio_layer": gv["ms_per_step"] / g["ms_per_step"],
+                          "ratio_expert": (kv["gemm1"] + kv["gemm2"] + kv["combine"]) / expert_ms}
+            log(vname, van[vname])
+            del gv, vin
+            torch.cuda.empty_cache()
+        result["vanilla"] = van
+        result["ideal_ratio_rows"] = shape.T * shape.k / max(g["R"], 1)
+        result["tab1_fraction_tau1"] = ffn_work_fraction(1.0, shape.n_ffn, shape.n_zc)
+        result["paper_context"] = "paper Tab.3: 1.1-2.1x expert forward throughput vs vanilla MoE " \
+                                  "(A100 cluster, other shapes); context only"
+
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a sample")
+        result["cpu_baseline"] = cpu_baseline(shape, inp)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

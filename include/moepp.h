@@ -199,11 +199,13 @@ moepp_status moepp_get_intermediates(moepp_ctx *ctx, const float **alpha1,
                                      const void **h, const void **yffn);
 
 /*
- * Per-kernel timing.  With timing enabled, every step records HIP events on
- * the call's stream around each kernel it launches.  moepp_get_timing waits
- * for the last recorded event (host synchronisation) and writes the duration
- * in milliseconds of each kernel of the last call into ms[MOEPP_NUM_KERNELS]
- * (host array; 0 for kernels that did not run).
+ * Per-kernel timing.  With timing enabled, every call records HIP events on
+ * its stream around each kernel it launches (up to 64 calls are kept, later
+ * ones overwrite the oldest).  moepp_get_timing waits for the recorded events
+ * (host synchronisation), writes into ms[MOEPP_NUM_KERNELS] (host array) the
+ * duration in milliseconds of each kernel averaged over the calls recorded
+ * since timing was enabled or last read (0 for kernels that did not run), and
+ * starts a new average.
  */
 enum {
     MOEPP_K_ROUTER = 0,  /* router GEMM + residual + softmax + top-k         */

@@ -8,6 +8,8 @@
 
 using namespace moepp;
 
+constexpr int kTimingSlots = 64;
+
 struct moepp_ctx {
     moepp_desc desc;
     Workspace ws;
@@ -17,8 +19,11 @@ struct moepp_ctx {
     int last_T, last_k;
     bool timing;
     bool have_events;
-    hipEvent_t ev[MOEPP_NUM_KERNELS][2];
-    bool ran[MOEPP_NUM_KERNELS];
+    // ring of event pairs: one slot per recorded call
+    hipEvent_t ev[kTimingSlots][MOEPP_NUM_KERNELS][2];
+    bool ran[kTimingSlots][MOEPP_NUM_KERNELS];
+    int slot;             // slot of the call being recorded
+    int n_recorded;       // calls recorded since the last moepp_get_timing
 };
 
 namespace {
@@ -100,19 +105,30 @@ struct KernelTimer {
     int which;
     KernelTimer(moepp_ctx *c_, hipStream_t s_, int which_) : c(c_), s(s_), which(which_) {
         if (c->timing && c->have_events) {
-            (void)hipEventRecord(c->ev[which][0], s);
+            (void)hipEventRecord(c->ev[c->slot][which][0], s);
         }
     }
     ~KernelTimer() {
         if (c->timing && c->have_events) {
-            (void)hipEventRecord(c->ev[which][1], s);
-            c->ran[which] = true;
+            (void)hipEventRecord(c->ev[c->slot][which][1], s);
+            c->ran[c->slot][which] = true;
         }
     }
 };
 
+// Start recording a new call: take the next slot of the ring.
 void reset_ran(moepp_ctx *c) {
-    for (int i = 0; i < MOEPP_NUM_KERNELS; ++i) c->ran[i] = false;
+    if (!(c->timing && c->have_events)) return;
+    c->slot = (c->slot + 1) % kTimingSlots;
+    if (c->n_recorded < kTimingSlots) c->n_recorded += 1;
+    for (int i = 0; i < MOEPP_NUM_KERNELS; ++i) c->ran[c->slot][i] = false;
+}
+
+void clear_timing(moepp_ctx *c) {
+    c->slot = kTimingSlots - 1;
+    c->n_recorded = 0;
+    for (int q = 0; q < kTimingSlots; ++q)
+        for (int i = 0; i < MOEPP_NUM_KERNELS; ++i) c->ran[q][i] = false;
 }
 
 bool use_mfma_router(const moepp_ctx *c, const Dims &d, moepp_status *st) {
@@ -280,7 +296,7 @@ moepp_status moepp_create(const moepp_desc *desc, void *workspace, size_t bytes,
     c->last_k = desc->k;
     c->timing = false;
     c->have_events = false;
-    reset_ran(c);
+    clear_timing(c);
     *ctx = c;
     return MOEPP_OK;
 }
@@ -288,10 +304,11 @@ moepp_status moepp_create(const moepp_desc *desc, void *workspace, size_t bytes,
 moepp_status moepp_destroy(moepp_ctx *ctx) {
     if (!ctx) return MOEPP_EINVAL;
     if (ctx->have_events)
-        for (int i = 0; i < MOEPP_NUM_KERNELS; ++i) {
-            (void)hipEventDestroy(ctx->ev[i][0]);
-            (void)hipEventDestroy(ctx->ev[i][1]);
-        }
+        for (int q = 0; q < kTimingSlots; ++q)
+            for (int i = 0; i < MOEPP_NUM_KERNELS; ++i) {
+                (void)hipEventDestroy(ctx->ev[q][i][0]);
+                (void)hipEventDestroy(ctx->ev[q][i][1]);
+            }
     delete ctx;
     return MOEPP_OK;
 }
@@ -421,13 +438,14 @@ moepp_status moepp_get_intermediates(moepp_ctx *ctx, const float **alpha1, const
 moepp_status moepp_set_timing(moepp_ctx *ctx, int32_t enable) {
     if (!ctx) return MOEPP_EINVAL;
     if (enable && !ctx->have_events) {
-        for (int i = 0; i < MOEPP_NUM_KERNELS; ++i)
-            for (int j = 0; j < 2; ++j)
-                if (hipEventCreate(&ctx->ev[i][j]) != hipSuccess) return MOEPP_EHIP;
+        for (int q = 0; q < kTimingSlots; ++q)
+            for (int i = 0; i < MOEPP_NUM_KERNELS; ++i)
+                for (int j = 0; j < 2; ++j)
+                    if (hipEventCreate(&ctx->ev[q][i][j]) != hipSuccess) return MOEPP_EHIP;
         ctx->have_events = true;
     }
     ctx->timing = enable != 0;
-    reset_ran(ctx);
+    clear_timing(ctx);
     return MOEPP_OK;
 }
 
@@ -435,12 +453,21 @@ moepp_status moepp_get_timing(moepp_ctx *ctx, float *ms) {
     if (!ctx || !ms) return MOEPP_EINVAL;
     for (int i = 0; i < MOEPP_NUM_KERNELS; ++i) {
         ms[i] = 0.f;
-        if (ctx->have_events && ctx->ran[i]) {
-            if (hipEventSynchronize(ctx->ev[i][1]) != hipSuccess) return MOEPP_EHIP;
-            if (hipEventElapsedTime(&ms[i], ctx->ev[i][0], ctx->ev[i][1]) != hipSuccess)
+        if (!ctx->have_events) continue;
+        double sum = 0.0;
+        int n = 0;
+        for (int q = 0; q < kTimingSlots; ++q) {
+            if (!ctx->ran[q][i]) continue;
+            float t = 0.f;
+            if (hipEventSynchronize(ctx->ev[q][i][1]) != hipSuccess) return MOEPP_EHIP;
+            if (hipEventElapsedTime(&t, ctx->ev[q][i][0], ctx->ev[q][i][1]) != hipSuccess)
                 return MOEPP_EHIP;
+            sum += t;
+            n += 1;
         }
+        if (n) ms[i] = (float)(sum / n);
     }
+    clear_timing(ctx);
     return MOEPP_OK;
 }
 
