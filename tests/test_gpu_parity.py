@@ -219,7 +219,7 @@ def _full_size(name, n_sample, check_inter=True):
     say("workload", name, s)
     inp = make_inputs(s)
     say("inputs ready")
-    res = gpu_forward(s, inp, variant=0)
+    res = gpu_forward(s, inp, variant=2)      # the MFMA kernels must cover every benchmark shape
     say("gpu done, R =", int(res["offsets"][-1]), "counts", res["counts"].tolist())
     toks = None if n_sample is None else sample_tokens(s, res["topk_idx"], n_sample, seed=s.seed)
     errs = check_layer(s, inp, res, tok_list=toks, check_inter=check_inter)
