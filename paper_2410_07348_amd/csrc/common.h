@@ -102,6 +102,15 @@ hipError_t launch_pack(const Dims &d, bool bf16, const void *w1, const void *w3,
                        const void *w2, void *w13_out, void *w2_out, hipStream_t s);
 
 // ---- small device helpers -------------------------------------------------
+// Workgroup barrier that orders LDS accesses only: global loads (including
+// loads that write LDS directly, which the caller waits for with vmcnt) stay
+// in flight across it, unlike __syncthreads().
+__device__ inline void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __device__ inline float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

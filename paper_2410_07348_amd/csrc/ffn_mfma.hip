@@ -24,6 +24,10 @@
 // same lane, so SwiGLU is applied in registers.
 #include "common.h"
 
+#include <stdlib.h>
+
+#include <type_traits>
+
 namespace moepp {
 
 struct GemmArgs {
@@ -40,24 +44,56 @@ struct GemmArgs {
     int n_ntiles;
 };
 
-constexpr int BK = 64;                 // K elements per LDS tile (128 bytes per row)
-constexpr int kRowBytes = BK * 2;
-
 __device__ inline float fast_silu(float z) { return z * __frcp_rn(1.f + __expf(-z)); }
 
-template <int BM, int BN, int WM, int WN, bool SWIGLU>
-__global__ __launch_bounds__(WM *WN *kWave, 1) void k_grouped_gemm(GemmArgs a) {
-    constexpr int NT = WM * WN * kWave;
-    constexpr int TM = BM / WM, TN = BN / WN;     // wave tile
-    constexpr int MB = TM / 32, NB = TN / 32;     // 32x32 blocks per wave
-    constexpr int CA = BM * 8 / NT, CB = BN * 8 / NT;   // 16-byte chunks per thread
-    constexpr int STAGE = (BM + BN) * kRowBytes;
+typedef const __attribute__((address_space(1))) void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+// Tile geometry.  BK K-elements per LDS stage; NS stages form a ring, NS - 1
+// tiles are in flight (or being computed) at any time.
+template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_>
+struct Geo {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
+    static constexpr int NT = WM * WN * kWave;         // threads
+    static constexpr int RB = BK * 2;                  // bytes per tile row
+    static constexpr int CPR = RB / 16;                // 16-byte slots per tile row
+    static constexpr int TM = BM / WM, TN = BN / WN;   // wave tile
+    static constexpr int MB = TM / 32, NB = TN / 32;   // 32x32 MFMA blocks per wave
+    static constexpr int CA = BM * CPR / NT, CB = BN * CPR / NT;   // loads per thread and tile
+    static constexpr int STAGE = (BM + BN) * RB;
+    static constexpr int KS = BK / 16;                 // MFMA K steps per stage
+    static_assert(TM % 32 == 0 && TN % 64 == 0, "wave tile");
+    static_assert((BM * CPR) % NT == 0 && (BN * CPR) % NT == 0 && (NT / CPR) % 16 == 0, "chunks");
+    static_assert(BK == 32 || BK == 64, "BK");
+    // XOR swizzle of the 16-byte slots of a tile row.  The LDS has 64 banks of
+    // 4 bytes (256 bytes), and a b128 operand read is served 16 lanes at a
+    // time; with this swizzle any 16 consecutive tile rows read at the same
+    // logical slot land on 16 different bank groups.
+    __device__ static int swz(int row) { return (row / (256 / RB)) % CPR; }
+};
+
+// s_waitcnt vmcnt(VM) lgkmcnt(0), then the workgroup barrier.  The wait is
+// the builtin (so the compiler's own counter tracking sees it) and the empty
+// asm statements keep every memory access on its side of the barrier; no
+// fence builtin is used because it would also wait for the younger
+// direct-to-LDS loads, which count as LDS writes.
+template <int VM>
+__device__ inline void wait_and_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt((VM & 15) | 0x70 | ((VM >> 4) << 14));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <class G, bool SWIGLU>
+__global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
+    constexpr int BM = G::BM, BN = G::BN, WN = G::WN, NT = G::NT, RB = G::RB, CPR = G::CPR;
+    constexpr int TM = G::TM, TN = G::TN, MB = G::MB, NB = G::NB, CA = G::CA, CB = G::CB;
+    constexpr int STAGE = G::STAGE, NS = G::NS, BK = G::BK, KS = G::KS;
     constexpr int OUT_W = SWIGLU ? BN / 2 : BN;   // output tile width (elements)
     constexpr int OUT_STRIDE = OUT_W * 2 + 16;    // bytes, padded
     constexpr int OUT_BYTES = BM * OUT_STRIDE;
-    constexpr int LDS_BYTES = 2 * STAGE > OUT_BYTES ? 2 * STAGE : OUT_BYTES;
-    static_assert(TM % 32 == 0 && TN % 64 == 0, "wave tile");
-    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && (NT / 8) % 8 == 0, "chunks");
+    constexpr int LDS_BYTES = NS * STAGE > OUT_BYTES ? NS * STAGE : OUT_BYTES;
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
 
     const int tid = threadIdx.x;
@@ -66,35 +102,60 @@ __global__ __launch_bounds__(WM *WN *kWave, 1) void k_grouped_gemm(GemmArgs a) {
     const int wm = wave / WN, wn = wave % WN;
 
     // ---- which tile --------------------------------------------------------
-    const int nt = blockIdx.x % a.n_ntiles;
-    const int mt = blockIdx.x / a.n_ntiles;
-    int e = 0, row0 = 0, row_end = 0;
+    // Workgroups are handed to the 8 XCDs round-robin by id, and every XCD has
+    // its own L2.  All tiles are put in one linear order in which 32
+    // consecutive tiles form a patch of GM m-tiles x GN n-tiles of one expert
+    // (they share GM + GN operand panels instead of 64), and XCD x works
+    // through the x-th eighth of that order: workgroup w is the (w / 8)-th
+    // tile of XCD w % 8.  The order is computed here from the group offsets.
+    constexpr int GM = 8, GN = 4, NXCD = 8;
+    int e = 0, row0 = 0, row_end = 0, nt = 0;
     {
-        int acc_t = 0;
-        bool found = false;
+        const int Nt = a.n_ntiles;
+        int total_mt = 0;
+        for (int q = 0; q < a.n_ffn; ++q) total_mt += (a.offsets[q + 1] - a.offsets[q] + BM - 1) / BM;
+        const int total = total_mt * Nt;
+        const int chunk = (total + NXCD - 1) / NXCD;
+        const int j = blockIdx.x / NXCD;
+        int L = (blockIdx.x % NXCD) * chunk + j;        // linear tile index
+        if (j >= chunk || L >= total) return;
+        int mt_e = 0, b = 0;
         for (e = 0; e < a.n_ffn; ++e) {
-            const int b = a.offsets[e], en = a.offsets[e + 1];
-            const int nte = (en - b + BM - 1) / BM;
-            if (mt < acc_t + nte) {
-                row0 = b + (mt - acc_t) * BM;
-                row_end = en;
-                found = true;
-                break;
-            }
-            acc_t += nte;
+            b = a.offsets[e];
+            row_end = a.offsets[e + 1];
+            mt_e = (row_end - b + BM - 1) / BM;
+            if (L < mt_e * Nt) break;
+            L -= mt_e * Nt;
         }
-        if (!found) return;
+        // inside expert e: m-groups of GM m-tiles, n-groups of GN n-tiles, m fastest
+        const int n_g = (mt_e + GM - 1) / GM;
+        int g = L / (GM * Nt);
+        g = g < n_g - 1 ? g : n_g - 1;
+        const int gm = g < n_g - 1 ? GM : mt_e - GM * (n_g - 1);
+        L -= g * GM * Nt;
+        const int NG = (Nt + GN - 1) / GN;
+        int ng = L / (gm * GN);
+        ng = ng < NG - 1 ? ng : NG - 1;
+        L -= ng * gm * GN;
+        const int mt = g * GM + L % gm;
+        nt = ng * GN + L / gm;
+        row0 = b + mt * BM;
     }
     const int n0 = nt * BN;
 
-    // ---- global -> register -> LDS staging ----------------------------------
-    const int kc = tid % 8;              // 16-byte chunk within the 128-byte tile row
-    const int r_thr = tid / 8;           // tile row of this thread's first chunk
+    // ---- global -> LDS, written by the load itself ----------------------------
+    // Chunk c = tid + i*NT of a tile: row c/CPR, 16-byte slot c%CPR.  One
+    // wave-wide load fills 1 KB of consecutive tile rows: lane l lands at
+    // base + 16*l.  Slot s of row r holds global chunk s ^ swz(r) of that row,
+    // so each lane fetches the global chunk that belongs in its slot.
+    const int slot = tid % CPR;
+    const int r_thr = tid / CPR;                 // tile row of this thread's first chunk
+    const int kc = slot ^ G::swz(r_thr);         // global chunk within the K tile
     const bf16_t *pa[CA];
     const bf16_t *pb[CB];
 #pragma unroll
     for (int i = 0; i < CA; ++i) {
-        int r = row0 + r_thr + i * (NT / 8);
+        int r = row0 + r_thr + i * (NT / CPR);
         r = r < row_end ? r : row_end - 1;
         const int src = SWIGLU ? a.src_of[r] / a.topk : r;
         pa[i] = a.A + (size_t)src * a.lda + kc * 8;
@@ -102,38 +163,34 @@ __global__ __launch_bounds__(WM *WN *kWave, 1) void k_grouped_gemm(GemmArgs a) {
     const bf16_t *Be = a.B + (size_t)e * a.Nb * a.K;
 #pragma unroll
     for (int i = 0; i < CB; ++i) {
-        int n = n0 + r_thr + i * (NT / 8);
+        int n = n0 + r_thr + i * (NT / CPR);
         n = n < a.Nb ? n : a.Nb - 1;
         pb[i] = Be + (size_t)n * a.K + kc * 8;
     }
-    const int st_off = r_thr * kRowBytes + ((kc ^ (r_thr & 7)) << 4);
+    const int wave_off = __builtin_amdgcn_readfirstlane(wave) * 1024;   // this wave's 1 KB of each load group
 
-    bf16x8 ra[CA], rb[CB];
-    auto load_tile = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < CA; ++i) ra[i] = *reinterpret_cast<const bf16x8 *>(pa[i] + kt * BK);
-#pragma unroll
-        for (int i = 0; i < CB; ++i) rb[i] = *reinterpret_cast<const bf16x8 *>(pb[i] + kt * BK);
-    };
-    auto store_tile = [&](int stage) {
-        char *sa = lds + stage * STAGE;
-        char *sb = sa + BM * kRowBytes;
+    auto issue_tile = [&](int kt, char *__restrict__ stage) {
+        char *sa = stage + wave_off;
+        char *sb = sa + BM * RB;
 #pragma unroll
         for (int i = 0; i < CA; ++i)
-            *reinterpret_cast<bf16x8 *>(sa + st_off + i * (NT / 8) * kRowBytes) = ra[i];
+            __builtin_amdgcn_global_load_lds((gptr_t)(pa[i] + kt * BK),
+                                             (lptr_t)(sa + i * (NT / CPR) * RB), 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < CB; ++i)
-            *reinterpret_cast<bf16x8 *>(sb + st_off + i * (NT / 8) * kRowBytes) = rb[i];
+            __builtin_amdgcn_global_load_lds((gptr_t)(pb[i] + kt * BK),
+                                             (lptr_t)(sb + i * (NT / CPR) * RB), 16, 0, 0);
     };
 
     // ---- MFMA operand addressing --------------------------------------------
     // lane l reads row (l % 32) of a 32-row block, K half (l / 32) of each 16-wide step
     const int l32 = lane % 32, lh = lane / 32;
-    int rd_off[4];
+    int rd_off[KS];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) rd_off[ks] = l32 * kRowBytes + (((2 * ks + lh) ^ (l32 & 7)) << 4);
-    const int a_base = (wm * TM) * kRowBytes;
-    const int b_base = BM * kRowBytes + (wn * TN) * kRowBytes;
+    for (int ks = 0; ks < KS; ++ks)
+        rd_off[ks] = l32 * RB + (((2 * ks + lh) ^ G::swz(l32)) << 4);
+    const int a_base = (wm * TM) * RB;
+    const int b_base = BM * RB + (wn * TN) * RB;
 
     f32x16 acc[NB][MB];
 #pragma unroll
@@ -143,37 +200,130 @@ __global__ __launch_bounds__(WM *WN *kWave, 1) void k_grouped_gemm(GemmArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.f;
 
-    const int KT = a.K / BK;
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 1 < KT;
-        if (more) load_tile(kt + 1);
-        const char *s = lds + (kt & 1) * STAGE;
+    auto read_frags = [&](const char *st, int ks, bf16x8 *fa, bf16x8 *fb) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 fa[MB], fb[NB];
+        for (int i = 0; i < MB; ++i)
+            fa[i] = *reinterpret_cast<const bf16x8 *>(st + a_base + i * 32 * RB + rd_off[ks]);
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            fb[j] = *reinterpret_cast<const bf16x8 *>(st + b_base + j * 32 * RB + rd_off[ks]);
+    };
+    auto mfma_step = [&](const bf16x8 *fa, const bf16x8 *fb) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int i = 0; i < MB; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8 *>(s + a_base + i * 32 * kRowBytes + rd_off[ks]);
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[j][i], 0, 0, 0);
+    };
+
+    const int KT = a.K / BK;
+    constexpr int LPT = CA + CB;            // loads per thread and tile
+    // prologue: tiles 0 .. NS-2 in flight
 #pragma unroll
-            for (int j = 0; j < NB; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8 *>(s + b_base + j * 32 * kRowBytes + rd_off[ks]);
+    for (int p = 0; p < NS - 1; ++p)
+        if (p < KT) issue_tile(p, lds + p * STAGE);
+
+    if constexpr (NS >= 3) {
+        // Ring of NS stages, tile kt in stage kt % NS.  The workgroup barrier
+        // sits before the LAST MFMA step of a tile, not after it: once every
+        // wave has issued (and received) all operand reads of tile kt, the
+        // stage of tile kt-1 can be refilled and the first operands of tile
+        // kt+1 can be read, all while the matrix cores still work on the last
+        // step of tile kt.  Operands are double buffered in registers.  The
+        // loop body is branch-free (the last NS-1 tiles are peeled off), which
+        // keeps the compiler's wait-count tracking exact.  Needs KT >= NS-1.
+        static_assert(KS % 2 == 0, "operand double buffering assumes an even number of K steps");
+        bf16x8 fa[2][MB], fb[2][NB];
+        // One tile.  cur / nxt / wr are three different stages (restrict): the
+        // loads that refill wr never make the operand reads wait.  VM = loads of
+        // younger tiles that may still be in flight when tile kt+1 is needed.
+        auto k_tile = [&](const char *__restrict__ cur, const char *__restrict__ nxt,
+                          char *__restrict__ wr, int kt_issue, auto vm_c, auto issue_c, auto last_c) {
+            constexpr int VM = decltype(vm_c)::value;
+            constexpr bool ISSUE = decltype(issue_c)::value, LAST = decltype(last_c)::value;
 #pragma unroll
-            for (int j = 0; j < NB; ++j)
-#pragma unroll
-                for (int i = 0; i < MB; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[j][i], 0, 0, 0);
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) {
+                    read_frags(cur, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+                } else if constexpr (!LAST) {
+                    wait_and_barrier<VM>();   // tile kt+1 landed; my reads of tile kt complete
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (ISSUE) issue_tile(kt_issue, wr);
+                    read_frags(nxt, 0, fa[0], fb[0]);
+                    // keep these reads ahead of the MFMAs below: they fly while
+                    // the matrix cores work on the last step of this tile
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                mfma_step(fa[ks & 1], fb[ks & 1]);
+            }
+        };
+        int s_cur = 0, s_nxt = 1, s_wr = NS - 1;
+        auto rotate = [&]() {
+            s_wr = s_cur;
+            s_cur = s_nxt;
+            s_nxt = s_nxt + 1 == NS ? 0 : s_nxt + 1;
+        };
+        typedef std::true_type yes_t;
+        typedef std::false_type no_t;
+        wait_and_barrier<(NS - 2) * LPT>();     // tile 0 landed
+        read_frags(lds, 0, fa[0], fb[0]);
+        for (int kt = 0; kt < KT - (NS - 1); ++kt) {
+            k_tile(lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, kt + NS - 1,
+                   std::integral_constant<int, (NS - 3) * LPT>{}, yes_t{}, no_t{});
+            rotate();
         }
-        if (more) store_tile((kt + 1) & 1);
-        __syncthreads();
+        // the last NS-1 tiles: nothing left to issue, fewer loads in flight
+        auto tail = [&](auto t_c) {
+            constexpr int t = decltype(t_c)::value;
+            if constexpr (t < NS - 1) {
+                constexpr int younger = NS - 3 - t > 0 ? NS - 3 - t : 0;
+                k_tile(lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, 0,
+                       std::integral_constant<int, younger * LPT>{}, no_t{},
+                       std::integral_constant<bool, t == NS - 2>{});
+                rotate();
+            }
+        };
+        tail(std::integral_constant<int, 0>{});
+        tail(std::integral_constant<int, 1>{});
+        tail(std::integral_constant<int, 2>{});
+        tail(std::integral_constant<int, 3>{});
+        static_assert(NS <= 5, "tail unrolling covers NS - 1 <= 4 tiles");
+    } else {
+        // Two stages: refill the stage that was computed last with the next
+        // tile, then run the MFMAs of this one.  `rd` and `wr` never overlap
+        // (restrict), so the operand reads are not made to wait on those loads.
+        auto k_tile = [&](const char *__restrict__ rd, char *__restrict__ wr, int kt_issue, bool issue) {
+            if (issue) issue_tile(kt_issue, wr);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                bf16x8 fa[MB], fb[NB];
+                read_frags(rd, ks, fa, fb);
+                mfma_step(fa, fb);
+            }
+        };
+        int st_rd = 0, st_wr = NS - 1;      // ring positions: tile kt lives in stage kt % NS
+        for (int kt = 0; kt < KT; ++kt) {
+            // Tile kt has landed when the loads of the younger tiles are the
+            // only ones outstanding.  The wait, the barrier and the compiler
+            // fence are one asm block so that nothing else makes this wave wait
+            // for the younger loads (a fence builtin would: those loads are LDS
+            // writes too).  lgkmcnt(0): this wave's operand reads of the
+            // previous tile are complete before any wave refills that stage.
+            if (kt + NS - 2 < KT)
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * LPT) : "memory");
+            else
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            k_tile(lds + st_rd * STAGE, lds + st_wr * STAGE, kt + NS - 1, kt + NS - 1 < KT);
+            st_rd = st_rd + 1 == NS ? 0 : st_rd + 1;
+            st_wr = st_wr + 1 == NS ? 0 : st_wr + 1;
+        }
     }
+    __syncthreads();                        // all waves done reading the stages
 
     // ---- epilogue: registers -> LDS tile -> 16-byte row-contiguous stores ----
     // acc[j][i][v]: output row m = wm*TM + i*32 + l32,
     //               B row n = wn*TN + j*32 + 8*(v/4) + 4*lh + v%4
-    // (the last loop iteration ended with a barrier: all waves are done reading)
+    typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
         const int m = wm * TM + i * 32 + l32;
@@ -184,7 +334,6 @@ __global__ __launch_bounds__(WM *WN *kWave, 1) void k_grouped_gemm(GemmArgs a) {
                 const int c0 = (wn * TN + j * 32) / 2 + 4 * lh;   // 32 columns per block pair
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
                     bf16x4 o;
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
@@ -198,7 +347,6 @@ __global__ __launch_bounds__(WM *WN *kWave, 1) void k_grouped_gemm(GemmArgs a) {
                 const int c0 = wn * TN + j * 32 + 4 * lh;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
                     bf16x4 o;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) o[q] = (bf16_t)acc[j][i][4 * g + q];
@@ -208,10 +356,10 @@ __global__ __launch_bounds__(WM *WN *kWave, 1) void k_grouped_gemm(GemmArgs a) {
         }
     }
     __syncthreads();
-    constexpr int CPR = OUT_W / 8;                 // 16-byte chunks per output row
+    constexpr int OCPR = OUT_W / 8;                // 16-byte chunks per output row
     const int c_col0 = SWIGLU ? n0 / 2 : n0;
-    for (int c = tid; c < BM * CPR; c += NT) {
-        const int m = c / CPR, cc = c % CPR;
+    for (int c = tid; c < BM * OCPR; c += NT) {
+        const int m = c / OCPR, cc = c % OCPR;
         const int row = row0 + m, col = c_col0 + cc * 8;
         if (row < row_end && col < a.Nc)
             *reinterpret_cast<bf16x8 *>(a.C + (size_t)row * a.ldc + col) =
@@ -219,9 +367,9 @@ __global__ __launch_bounds__(WM *WN *kWave, 1) void k_grouped_gemm(GemmArgs a) {
     }
 }
 
-bool ffn_mfma_supported(const Dims &d) { return d.D % BK == 0 && d.F % BK == 0; }
+bool ffn_mfma_supported(const Dims &d) { return d.D % 64 == 0 && d.F % 64 == 0; }
 
-template <int BM, int BN, int WM, int WN>
+template <class G>
 static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
     GemmArgs a;
     a.offsets = f.offsets;
@@ -247,22 +395,33 @@ static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
         a.ldc = f.d.D;
         a.Nc = f.d.D;
     }
+    constexpr int BM = G::BM, BN = G::BN;
     a.n_ntiles = (a.Nb + BN - 1) / BN;
     const long long rows = (long long)f.d.T * f.d.k;
     const long long max_mtiles = (rows + BM - 1) / BM + f.d.n_ffn;   // upper bound of sum ceil(count_e/BM)
-    const long long blocks = max_mtiles * a.n_ntiles;
+    const long long blocks = (max_mtiles * a.n_ntiles + 7) / 8 * 8;   // whole rounds over the 8 XCDs
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    dim3 grid((unsigned)blocks), block(WM * WN * kWave);
+    dim3 grid((unsigned)blocks), block(G::NT);
     if (which == 0)
-        hipLaunchKernelGGL((k_grouped_gemm<BM, BN, WM, WN, true>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_grouped_gemm<G, true>), grid, block, 0, s, a);
     else
-        hipLaunchKernelGGL((k_grouped_gemm<BM, BN, WM, WN, false>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_grouped_gemm<G, false>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
     if (f.d.T == 0 || f.d.n_ffn == 0) return hipSuccess;
-    return launch_cfg<256, 256, 2, 4>(f, which, s);
+    // tuning knob: MOEPP_GEMM_CFG selects a tile configuration (default 0)
+    const char *v = getenv("MOEPP_GEMM_CFG");
+    int cfg = v ? atoi(v) : 0;
+    const int K = which == 0 ? f.d.D : f.d.F;
+    if (K / 32 < 4) cfg = 0;              // too few K tiles to fill a ring of stages
+    switch (cfg) {
+        case 1: return launch_cfg<Geo<256, 256, 2, 4, 32, 4>>(f, which, s);
+        case 2: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);
+        case 3: return launch_cfg<Geo<256, 256, 2, 4, 32, 3>>(f, which, s);
+        default: return launch_cfg<Geo<256, 256, 2, 4, 64, 2>>(f, which, s);
+    }
 }
 
 }  // namespace moepp

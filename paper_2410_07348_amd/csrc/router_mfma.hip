@@ -29,13 +29,6 @@ constexpr int kRtTok = 32 * kRtWaves;      // tokens per workgroup
 constexpr int kRtKC = 256;                 // K elements per LDS chunk
 constexpr int kRtRowBytes = kRtKC * 2;     // one weight row of one piece in LDS
 
-// LDS-only workgroup barrier: global loads stay in flight across it.
-__device__ inline void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
 template <int NBLK>   // 32-row blocks of weight rows
 __global__ __launch_bounds__(kRtWaves *kWave, 1) void k_router_mfma(RouterArgs a) {
     constexpr int ROWS = NBLK * 32;
