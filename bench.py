@@ -97,6 +97,19 @@ def roofline_numbers(shape, g):
     return out
 
 
+def profiled_traffic(workload):
+    """HBM bytes per launch of each kernel, from the committed rocprofv3 --pmc
+    summary (FETCH_SIZE / WRITE_SIZE scaled by the copy kernel of known size);
+    counters cannot be read from inside this process, so this is the stored
+    figure for the same workload, or nothing."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {})
+    except OSError:
+        return {}
+
+
 def cpu_baseline(shape, inp, target_s=15.0):
     """The CPU oracle timed on a bounded sample of the workload's tokens."""
     import oracle
@@ -152,6 +165,10 @@ def main():
     km = g["kernel_ms"]
     expert_ms = km["gemm1"] + km["gemm2"] + km["combine"]
 
+    ceiling = M.mfma_ceiling() if shape.act == "bf16" else None
+    log("measured MFMA-only ceiling (random bf16 operands): %s TFLOP/s" % ceiling)
+    traffic = profiled_traffic(shape.name)
+
     result = {
         "metric": "moepp_layer_forward_tokens_per_s",
         "value": shape.T / (g["ms_per_step"] * 1e-3),
@@ -177,7 +194,10 @@ def main():
                               "bound": "mfma", "achieved": rf["gemm1_tflops"],
                               "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                               "frac": rf["gemm1_tflops"] / PEAK_BF16_MFMA_TFLOPS,
-                              "traffic": None}
+                              "traffic": traffic.get("gemm1"),
+                              "measured_mfma_ceiling_tflops": ceiling,
+                              "frac_of_measured_ceiling":
+                                  rf["gemm1_tflops"] / ceiling if ceiling else None}
     else:
         result["roofline"] = {"kernel": "k_combine", "bound": "hbm",
                               "achieved": rf["combine_gbs"], "peak": PEAK_HBM_GBS,

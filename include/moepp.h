@@ -228,6 +228,18 @@ moepp_status moepp_get_timing(moepp_ctx *ctx, float *ms);
  */
 moepp_status moepp_set_variant(moepp_ctx *ctx, int32_t variant);
 
+/*
+ * Measurement aid, not part of the layer: enqueues a kernel that does nothing
+ * but bf16 MFMAs on pseudo-random register operands (2 waves per SIMD, no
+ * memory traffic) and writes the number of floating-point operations it
+ * performs to *flops (host).  Timed by the caller, it gives the matrix rate
+ * this GPU sustains on real operand bits, which is below the published peak
+ * because the clock drops under matrix load.  `scratch` is a device buffer of
+ * at least 512 KiB (ENOMEM if smaller); iters >= 1 (about 0.1 ms per 200).
+ */
+moepp_status moepp_mfma_ceiling(void *stream, void *scratch, size_t scratch_bytes,
+                                int32_t iters, double *flops);
+
 const char *moepp_status_str(moepp_status status);
 
 #ifdef __cplusplus

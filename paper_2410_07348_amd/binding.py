@@ -16,7 +16,7 @@ EXPORTS = ("moepp_workspace_bytes", "moepp_packed_bytes", "moepp_create", "moepp
            "moepp_pack_experts", "moepp_set_router_bias", "moepp_layer_forward",
            "moepp_route", "moepp_permute", "moepp_expert_ffn", "moepp_combine",
            "moepp_get_routing", "moepp_get_intermediates", "moepp_set_timing",
-           "moepp_get_timing", "moepp_set_variant", "moepp_status_str")
+           "moepp_get_timing", "moepp_set_variant", "moepp_mfma_ceiling", "moepp_status_str")
 
 
 class MoeppError(RuntimeError):
@@ -79,6 +79,7 @@ def load_library(build_if_missing: bool = True):
     L.moepp_set_timing.argtypes = [vp, i32]
     L.moepp_get_timing.argtypes = [vp, POINTER(c_float)]
     L.moepp_set_variant.argtypes = [vp, i32]
+    L.moepp_mfma_ceiling.argtypes = [vp, vp, c_size_t, i32, POINTER(ctypes.c_double)]
     L.moepp_status_str.restype = c_char_p
     L.moepp_status_str.argtypes = [i32]
     for n in EXPORTS:
@@ -99,6 +100,27 @@ def _check(status, what):
 
 def _ptr(t):
     return None if t is None else c_void_p(t.data_ptr())
+
+
+def mfma_ceiling(iters=20000, reps=3, device="cuda:0"):
+    """Sustained bf16 MFMA rate (TFLOP/s) on pseudo-random operands, timed with
+    events on the current stream; the best of `reps` launches."""
+    import torch
+    L = load_library()
+    dev = torch.device(device)
+    scratch = torch.empty(512 * 1024, dtype=torch.uint8, device=dev)
+    flops = ctypes.c_double()
+    best = 0.0
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        stream = torch.cuda.current_stream(dev)
+        e0.record(stream)
+        _check(L.moepp_mfma_ceiling(c_void_p(stream.cuda_stream), _ptr(scratch), scratch.numel(),
+                                    iters, byref(flops)), "moepp_mfma_ceiling")
+        e1.record(stream)
+        e1.synchronize()
+        best = max(best, flops.value / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
 
 
 class Layer:

@@ -51,6 +51,7 @@ struct Workspace {
     int32_t *chunk_base; // [n_chunks*N]
     void *h;             // [T_max*k, F] act
     void *yffn;          // [T_max*k, D] act
+    void *wsplit;        // router_split_bytes(D, N + 2 n_const)
 };
 
 struct RouterArgs {
@@ -61,6 +62,7 @@ struct RouterArgs {
     int32_t *topk_idx;
     float *topk_w;
     float *alpha1;
+    void *wsplit;         // scratch of the MFMA router: bf16 pieces of the weight rows
 };
 
 struct FfnArgs {
@@ -87,6 +89,7 @@ struct CombineArgs {
 hipError_t launch_router_generic(const RouterArgs &a, bool bf16, hipStream_t s);
 bool router_mfma_supported(const Dims &d);
 hipError_t launch_router_mfma(const RouterArgs &a, hipStream_t s);
+size_t router_split_bytes(int D, int rows);
 
 hipError_t launch_perm_hist(const Dims &d, const Workspace &w, hipStream_t s);
 hipError_t launch_perm_scan(const Dims &d, const Workspace &w, hipStream_t s);
@@ -100,6 +103,10 @@ hipError_t launch_combine(const CombineArgs &a, bool bf16, hipStream_t s);
 
 hipError_t launch_pack(const Dims &d, bool bf16, const void *w1, const void *w3,
                        const void *w2, void *w13_out, void *w2_out, hipStream_t s);
+
+hipError_t launch_mfma_ceiling(float *scratch, int iters, hipStream_t s);
+double mfma_ceiling_flops(int iters);
+size_t mfma_ceiling_scratch_bytes();
 
 // ---- small device helpers -------------------------------------------------
 // Workgroup barrier that orders LDS accesses only: global loads (including

@@ -411,16 +411,18 @@ static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
 
 hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
     if (f.d.T == 0 || f.d.n_ffn == 0) return hipSuccess;
-    // tuning knob: MOEPP_GEMM_CFG selects a tile configuration (default 0)
+    // Default: 256x256 tile, 32-deep K stages in a ring of 5 (the whole 160 KB
+    // of LDS), which needs at least 4 K tiles; shorter reductions use two
+    // 64-deep stages.  MOEPP_GEMM_CFG (1..3) selects other geometries, for tuning.
     const char *v = getenv("MOEPP_GEMM_CFG");
     int cfg = v ? atoi(v) : 0;
     const int K = which == 0 ? f.d.D : f.d.F;
-    if (K / 32 < 4) cfg = 0;              // too few K tiles to fill a ring of stages
+    if (K / 32 < 4) cfg = 3;              // too few K tiles to fill a ring of stages
     switch (cfg) {
         case 1: return launch_cfg<Geo<256, 256, 2, 4, 32, 4>>(f, which, s);
-        case 2: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);
-        case 3: return launch_cfg<Geo<256, 256, 2, 4, 32, 3>>(f, which, s);
-        default: return launch_cfg<Geo<256, 256, 2, 4, 64, 2>>(f, which, s);
+        case 2: return launch_cfg<Geo<256, 256, 2, 4, 32, 3>>(f, which, s);
+        case 3: return launch_cfg<Geo<256, 256, 2, 4, 64, 2>>(f, which, s);
+        default: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);
     }
 }
 

@@ -72,6 +72,7 @@ size_t layout(const moepp_desc *d, char *base, Workspace *ws) {
     w.chunk_base = (int32_t *)take(chunks * N * 4);
     w.h = take(d->n_ffn ? slots * d->F * elt(d) : 0);
     w.yffn = take(d->n_ffn ? slots * d->D * elt(d) : 0);
+    w.wsplit = take(d->act == MOEPP_BF16 ? router_split_bytes(d->D, (int)N + 2 * d->n_const) : 0);
     if (ws) *ws = w;
     return off;
 }
@@ -163,6 +164,7 @@ moepp_status do_route(moepp_ctx *c, hipStream_t s, int T, const void *x, const f
     a.topk_idx = c->ws.topk_idx;
     a.topk_w = c->ws.topk_w;
     a.alpha1 = c->ws.alpha1;
+    a.wsplit = c->ws.wsplit;
     moepp_status st = MOEPP_OK;
     const bool mfma = use_mfma_router(c, a.d, &st);
     if (st != MOEPP_OK) return st;
@@ -469,6 +471,16 @@ moepp_status moepp_get_timing(moepp_ctx *ctx, float *ms) {
     }
     clear_timing(ctx);
     return MOEPP_OK;
+}
+
+moepp_status moepp_mfma_ceiling(void *stream, void *scratch, size_t scratch_bytes, int32_t iters,
+                                double *flops) {
+    if (!scratch || !flops || iters < 1 || misaligned(scratch)) return MOEPP_EINVAL;
+    if (scratch_bytes < mfma_ceiling_scratch_bytes()) return MOEPP_ENOMEM;
+    *flops = mfma_ceiling_flops(iters);
+    return launch_mfma_ceiling((float *)scratch, iters, (hipStream_t)stream) == hipSuccess
+               ? MOEPP_OK
+               : MOEPP_EHIP;
 }
 
 const char *moepp_status_str(moepp_status status) {
