@@ -255,7 +255,7 @@ __global__ __launch_bounds__(kRtThreads, 1) void k_router_mfma(RouterArgs a) {
         float mx = -INFINITY;
         for (int i = 0; i < N; ++i) mx = fmaxf(mx, Lr[i]);
         float sum = 0.f;
-        for (int i = 0; i < N; ++i) sum += expf(Lr[i] - mx);
+        for (int i = 0; i < N; ++i) sum += __expf(Lr[i] - mx);
         const float inv = 1.f / sum;
         unsigned long long taken = 0ull;
         const size_t t = (size_t)(t0 + tid);
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(kRtThreads, 1) void k_router_mfma(RouterArgs a) {
             }
             taken |= 1ull << bi;
             a.topk_idx[t * K + s] = bi;
-            a.topk_w[t * K + s] = expf(bv - mx) * inv;
+            a.topk_w[t * K + s] = __expf(bv - mx) * inv;
         }
         for (int j = 0; j < nc; ++j)
             a.alpha1[t * nc + j] = 1.f / (1.f + expf(Lr[N + 2 * j + 1] - Lr[N + 2 * j]));
