@@ -169,6 +169,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     }
     const int wave_off = __builtin_amdgcn_readfirstlane(wave) * 1024;   // this wave's 1 KB of each load group
 
+    const int KT = a.K / BK;
     auto issue_tile = [&](int kt, char *__restrict__ stage) {
         char *sa = stage + wave_off;
         char *sb = sa + BM * RB;
@@ -216,7 +217,6 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
                 acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[j][i], 0, 0, 0);
     };
 
-    const int KT = a.K / BK;
     constexpr int LPT = CA + CB;            // loads per thread and tile
     // prologue: tiles 0 .. NS-2 in flight
 #pragma unroll
@@ -419,7 +419,7 @@ hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
     const int K = which == 0 ? f.d.D : f.d.F;
     if (K / 32 < 4) cfg = 3;              // too few K tiles to fill a ring of stages
     switch (cfg) {
-        case 1: return launch_cfg<Geo<256, 256, 2, 4, 32, 4>>(f, which, s);
+        case 1: return launch_cfg<Geo<256, 256, 2, 2, 32, 5>>(f, which, s);
         case 2: return launch_cfg<Geo<256, 256, 2, 4, 32, 3>>(f, which, s);
         case 3: return launch_cfg<Geo<256, 256, 2, 4, 64, 2>>(f, which, s);
         default: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);

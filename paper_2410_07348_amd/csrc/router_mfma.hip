@@ -11,46 +11,32 @@
 // contraction runs as three bf16 MFMAs with float32 accumulation: products
 // are exact, logits keep float32-class accuracy.
 //
-// The kernel is a skinny GEMM [128 tokens x K] x [K x (N + 2 n_const)] per
-// workgroup of 8 waves.  x tiles of 64 K-elements are written into a ring of
-// LDS stages by the loads themselves (row-contiguous 16-byte chunks, so every
-// wave-wide load covers whole 128-byte lines).  The weight rows (router rows,
-// then the W_c rows) are split once per call by a small kernel into a scratch
-// buffer that already has the byte order of an LDS weight tile, so the weight
-// tile of a stage is filled by the same kind of load.  (A float32 load mixed
-// into the loop would have to be waited for with vmcnt, and loads complete in
-// order: it would drag every younger x load with it.)  Wave w owns tokens
-// 32 (w % 4) .. +31 and the K steps of parity w / 4 of every tile; the two
-// halves are added at the end.
+// The kernel is a skinny GEMM [TOK tokens x K] x [K x (N + 2 n_const)] per
+// workgroup of TOK / 16 waves (TOK = 128, or 64 when there are few tokens).  The weight rows (router rows, then the W_c rows) are
+// split once per call by a small kernel into a scratch buffer that already has
+// the byte order of an LDS weight tile.  x and weight tiles of 64 K-elements
+// are loaded with row-contiguous 16-byte chunks (every wave-wide load covers
+// whole 128-byte lines) into REGISTERS, PF tiles ahead, and stored from there
+// into a double-buffered LDS tile (the compiler tracks these ordinary loads
+// exactly, so nothing is waited for early); up to 8 tiles per thread are in
+// flight.  Workgroup b starts at K tile b % KT and wraps around, so that the
+// workgroups, which walk K in lockstep over rows a power of two apart, do not
+// all ask the same memory channels at the same time.  Wave w owns tokens
+// 32 (w % (TOK/32)) .. +31 and the K steps of parity w / (TOK/32) of every
+// tile; the two halves are added at the end.
 // Epilogue: gating residual and bias with all threads, then one thread per
 // token does softmax and Top-K on the float32 logits (ties to the lower
 // index, slots in descending order).
 #include "common.h"
 
-#include <type_traits>
-
 namespace moepp {
 
-constexpr int kRtThreads = 512;
-constexpr int kRtTok = 128;                // tokens per workgroup
 constexpr int kRtBK = 64;                  // K elements per stage
 constexpr int kRtRow = kRtBK * 2;          // bytes per tile row
-constexpr int kRtXBytes = kRtTok * kRtRow; // x part of a stage
-
-typedef const __attribute__((address_space(1))) void *rt_gptr_t;
-typedef __attribute__((address_space(3))) void *rt_lptr_t;
 
 // XOR swizzle of the 16-byte slots of a 128-byte tile row: 16 consecutive rows
 // read at one logical slot cover the 64 LDS banks exactly once.
 __device__ inline int rt_swz(int row) { return (row >> 1) & 7; }
-
-template <int VM>
-__device__ inline void rt_wait_and_barrier() {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt((VM & 15) | 0x70 | ((VM >> 4) << 14));   // vmcnt(VM) lgkmcnt(0)
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
 
 // Bytes of the split-weight scratch for a layer (0 if the MFMA router does not apply).
 size_t router_split_bytes(int D, int rows) {
@@ -93,57 +79,77 @@ __global__ __launch_bounds__(256) void k_router_split(RouterArgs a, int nblk) {
     *reinterpret_cast<bf16x4 *>(p + 2 * PIECE) = lo;
 }
 
-template <int NBLK>   // 32-row blocks of weight rows
-__global__ __launch_bounds__(kRtThreads, 1) void k_router_mfma(RouterArgs a) {
+// NBLK: 32-row blocks of weight rows; PF: tiles prefetched in registers;
+// TOK: tokens per workgroup (4 threads per token); WPE: waves per SIMD the
+// register budget is sized for (several small workgroups share a CU, so that
+// one can compute while another waits at its barrier).
+template <int NBLK, int PF, int TOK, int WPE>
+__global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
+    constexpr int kRtTok = TOK, kRtThreads = 4 * TOK, TB = TOK / 32;
+    constexpr int kRtXBytes = kRtTok * kRtRow;            // x part of a stage
     constexpr int ROWS = NBLK * 32;
     constexpr int PIECE = ROWS * kRtRow;                  // one bf16 piece of the weight tile
     constexpr int WBYTES = 3 * PIECE;                     // 12 KB per row block
-    constexpr int LPT = (kRtXBytes + WBYTES + kRtThreads * 16 - 1) / (kRtThreads * 16);   // loads per thread, tile
-    constexpr int STAGE = LPT * kRtThreads * 16;          // x tile, weight tile, padding
-    constexpr int NS = (160 * 1024) / STAGE < 4 ? (160 * 1024) / STAGE : 4;
+    constexpr int WCH = WBYTES / 16;                      // 16-byte chunks of a weight tile
+    constexpr int WL = (WCH + kRtThreads - 1) / kRtThreads;   // weight chunks per thread and tile
+    constexpr int STAGE = kRtXBytes + WBYTES;
     constexpr int DSTR = ROWS + 1;                        // floats per token in `dots`
     constexpr int E_BYTES = (2 * kRtTok * DSTR + kRtTok * (kMaxExperts + 1) +
                              kMaxExperts * kMaxExperts + kMaxExperts) * 4;
-    constexpr int LDS_BYTES = NS * STAGE > E_BYTES ? NS * STAGE : E_BYTES;
-    static_assert(NS >= 3 && LDS_BYTES <= 160 * 1024, "LDS");
+    constexpr int LDS_BYTES = 2 * STAGE > E_BYTES ? 2 * STAGE : E_BYTES;
+    static_assert(LDS_BYTES <= 160 * 1024 && PF % 2 == 0, "LDS / PF");
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
 
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int l32 = lane % 32, lh = lane / 32;
-    const int tb = wave % 4, kh = wave / 4;               // token block, K-step parity
+    const int tb = wave % TB, kh = wave / TB;             // token block, K-step parity
     const int D = a.d.D, N = a.d.N, K = a.d.k, nc = a.d.n_const, T = a.d.T;
     const int rows = N + 2 * nc;
     const int t0 = blockIdx.x * kRtTok;
-    const int KT = D / kRtBK;
+    const int KT = D / kRtBK;                             // a multiple of PF (the launcher checks)
 
-    // ---- loads that write LDS themselves: every thread issues LPT per tile ----
-    // chunk c = tid + 512 i.  c < 1024: x tile, row c / 8, slot c % 8 holds
-    // global chunk slot ^ swz(row).  Then the weight tile, a plain copy of the
-    // pre-split buffer; chunks past its end re-read its start (padding, unused).
-    const char *src[LPT];
-    int step[LPT];                                        // bytes from one K tile to the next
+    // ---- tile loads ------------------------------------------------------------
+    // x chunk c = tid + 512 i (i = 0, 1): tile row c / 8, LDS slot c % 8 holds
+    // global chunk slot ^ swz(row), so the LDS position of chunk c is simply 16 c.
+    // Weight chunk tid + 512 i: plain copy of the pre-split buffer.
+    const char *px[2];
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-        const int c = tid + kRtThreads * i;
-        if (c < kRtXBytes / 16) {
-            const int row = c / 8;
-            int tok = t0 + row;
-            tok = tok < T ? tok : T - 1;
-            src[i] = static_cast<const char *>(a.x) + ((size_t)tok * D + (((c % 8) ^ rt_swz(row)) << 3)) * 2;
-            step[i] = kRtBK * 2;
-        } else {
-            int wc = c - kRtXBytes / 16;
-            wc = wc < WBYTES / 16 ? wc : wc - WBYTES / 16;
-            src[i] = static_cast<const char *>(a.wsplit) + wc * 16;
-            step[i] = WBYTES;
-        }
+    for (int i = 0; i < 2; ++i) {
+        const int c = tid + kRtThreads * i, row = c / 8;
+        int tok = t0 + row;
+        tok = tok < T ? tok : T - 1;
+        px[i] = static_cast<const char *>(a.x) + ((size_t)tok * D + (((c % 8) ^ rt_swz(row)) << 3)) * 2;
     }
-    const int wave_off = __builtin_amdgcn_readfirstlane(wave) * 1024;
-    auto issue = [&](int kt, char *__restrict__ stage) {
+    const char *pw[WL];
 #pragma unroll
-        for (int i = 0; i < LPT; ++i)
-            __builtin_amdgcn_global_load_lds((rt_gptr_t)(src[i] + (size_t)kt * step[i]),
-                                             (rt_lptr_t)(stage + wave_off + i * kRtThreads * 16), 16, 0, 0);
+    for (int i = 0; i < WL; ++i) {
+        int wc = tid + kRtThreads * i;
+        wc = wc < WCH ? wc : tid;                         // surplus threads re-read a chunk, not stored
+        pw[i] = static_cast<const char *>(a.wsplit) + wc * 16;
+    }
+    bf16x8 xr[PF][2], wr[PF][WL];
+    // Workgroups walk K in lockstep, and rows of x are a power of two apart, so
+    // without a rotation every workgroup would ask the same few memory channels
+    // for its 128-byte pieces at the same time.  Workgroup b starts at K tile
+    // b % KT and wraps around (a dot product does not care about the order).
+    const int rot = blockIdx.x % KT;
+    auto load_regs = [&](int kt, bf16x8 *xq, bf16x8 *wq) {
+        kt = kt < KT ? kt : KT - 1;                       // past the end: harmless reload of the last tile
+        kt += rot;
+        kt = kt < KT ? kt : kt - KT;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) xq[i] = *reinterpret_cast<const bf16x8 *>(px[i] + (size_t)kt * (kRtBK * 2));
+#pragma unroll
+        for (int i = 0; i < WL; ++i) wq[i] = *reinterpret_cast<const bf16x8 *>(pw[i] + (size_t)kt * WBYTES);
+    };
+    auto store_regs = [&](char *stage, const bf16x8 *xq, const bf16x8 *wq) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            *reinterpret_cast<bf16x8 *>(stage + (tid + kRtThreads * i) * 16) = xq[i];
+#pragma unroll
+        for (int i = 0; i < WL; ++i)
+            if (tid + kRtThreads * i < WCH)               // wave-uniform: WCH is a multiple of 64
+                *reinterpret_cast<bf16x8 *>(stage + kRtXBytes + (tid + kRtThreads * i) * 16) = wq[i];
     };
 
     f32x16 acc_hi[NBLK], acc_lo[NBLK];
@@ -157,10 +163,7 @@ __global__ __launch_bounds__(kRtThreads, 1) void k_router_mfma(RouterArgs a) {
 #pragma unroll
     for (int s = 0; s < 2; ++s)
         rd_off[s] = l32 * kRtRow + (((2 * (2 * kh + s) + lh) ^ rt_swz(l32)) << 4);
-
-    // One tile: refill the stage that was read last, run the MFMAs of this one.
-    auto tile = [&](const char *__restrict__ cur, char *__restrict__ dst, int kt_issue, auto issue_c) {
-        if constexpr (decltype(issue_c)::value) issue(kt_issue, dst);
+    auto mfma_tile = [&](const char *cur) {
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const bf16x8 xf = *reinterpret_cast<const bf16x8 *>(cur + tb * 32 * kRtRow + rd_off[s]);
@@ -177,28 +180,25 @@ __global__ __launch_bounds__(kRtThreads, 1) void k_router_mfma(RouterArgs a) {
         }
     };
 
-    // Ring of NS stages, tile kt in stage kt % NS, NS - 1 tiles in flight.
-    // Needs KT >= NS - 1 (the launcher checks).
+    // Tile j waits in register slot j % PF and is computed from LDS stage j % 2.
+    // (Refilling slots in groups of consecutive K tiles, to hand DRAM longer
+    // contiguous runs, was measured and is slower than one tile per period.)
 #pragma unroll
-    for (int p = 0; p < NS - 1; ++p) issue(p, lds + p * STAGE);
-    rt_wait_and_barrier<(NS - 2) * LPT>();                   // tile 0 landed
-    int s_cur = 0, s_dst = NS - 1;
-    auto rotate = [&]() {
-        s_dst = s_cur;
-        s_cur = s_cur + 1 == NS ? 0 : s_cur + 1;
-    };
-    typedef std::true_type yes_t;
-    typedef std::false_type no_t;
-    for (int kt = 0; kt < KT - (NS - 1); ++kt) {
-        tile(lds + s_cur * STAGE, lds + s_dst * STAGE, kt + NS - 1, yes_t{});
-        rt_wait_and_barrier<(NS - 2) * LPT>();               // tile kt+1 landed, tile kt read by all
-        rotate();
-    }
+    for (int p = 0; p < PF; ++p) load_regs(p, xr[p], wr[p]);
+    store_regs(lds, xr[0], wr[0]);
+    load_regs(PF, xr[0], wr[0]);
+    lds_barrier();
+    for (int kt0 = 0; kt0 < KT; kt0 += PF) {
 #pragma unroll
-    for (int t = 0; t < NS - 1; ++t) {                       // the last NS-1 tiles: nothing to issue
-        tile(lds + s_cur * STAGE, lds + s_dst * STAGE, 0, no_t{});
-        rt_wait_and_barrier<0>();
-        rotate();
+        for (int s = 0; s < PF; ++s) {
+            const int kt = kt0 + s, q = (s + 1) % PF;     // q: slot of tile kt+1
+            // tile kt+1: registers -> the stage that tile kt-1 was read from (every
+            // wave passed the barrier after those reads), then refill the slot
+            store_regs(lds + ((s + 1) & 1) * STAGE, xr[q], wr[q]);
+            load_regs(kt + 1 + PF, xr[q], wr[q]);
+            mfma_tile(lds + (s & 1) * STAGE);
+            lds_barrier();                // tile kt+1 visible, tile kt read by all; loads stay in flight
+        }
     }
 
     // ---- epilogue -------------------------------------------------------------
@@ -284,8 +284,8 @@ __global__ __launch_bounds__(kRtThreads, 1) void k_router_mfma(RouterArgs a) {
 }
 
 bool router_mfma_supported(const Dims &d) {
-    // two 32-row blocks of weight rows at most; at least 3 K tiles to fill the ring
-    return d.D % kRtBK == 0 && d.D >= 3 * kRtBK && d.N + 2 * d.n_const <= 64;
+    // two 32-row blocks of weight rows at most; an even number of 64-wide K tiles
+    return d.D % (2 * kRtBK) == 0 && d.N + 2 * d.n_const <= 64;
 }
 
 hipError_t launch_router_mfma(const RouterArgs &a, hipStream_t s) {
@@ -294,11 +294,20 @@ hipError_t launch_router_mfma(const RouterArgs &a, hipStream_t s) {
     const int nblk = (rows + 31) / 32;
     const int n4 = nblk * 32 * (a.d.D / 4);
     hipLaunchKernelGGL(k_router_split, dim3((n4 + 255) / 256), dim3(256), 0, s, a, nblk);
-    dim3 grid((a.d.T + kRtTok - 1) / kRtTok), block(kRtThreads);
-    if (nblk == 1)
-        hipLaunchKernelGGL(k_router_mfma<1>, grid, block, 0, s, a);
-    else
-        hipLaunchKernelGGL(k_router_mfma<2>, grid, block, 0, s, a);
+    const int KT = a.d.D / kRtBK;
+    auto grid = [&](int tok) { return dim3((a.d.T + tok - 1) / tok); };
+    if (nblk == 1) {
+        // 128-token workgroups read the weight tiles half as often; 64-token ones
+        // fill the chip sooner when there are few tokens
+        if (KT % 8 == 0 && a.d.T >= 24576)
+            hipLaunchKernelGGL((k_router_mfma<1, 8, 128, 2>), grid(128), dim3(512), 0, s, a);
+        else if (KT % 4 == 0)
+            hipLaunchKernelGGL((k_router_mfma<1, 4, 64, 3>), grid(64), dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL((k_router_mfma<1, 2, 64, 3>), grid(64), dim3(256), 0, s, a);
+    } else {
+        hipLaunchKernelGGL((k_router_mfma<2, 2, 64, 2>), grid(64), dim3(256), 0, s, a);
+    }
     return hipGetLastError();
 }
 

@@ -180,3 +180,11 @@ def test_binding_has_no_cpu_fallback():
     assert "oracle" not in src
     with pytest.raises((FileNotFoundError, OSError)):
         ctypes.CDLL(os.path.join(ROOT, "paper_2410_07348_amd", "no_such_lib.so"))
+
+
+def test_mfma_ceiling_argument_checks(L):
+    flops = ctypes.c_double()
+    assert L.moepp_mfma_ceiling(None, None, 1 << 20, 100, byref(flops)) == B.EINVAL
+    assert L.moepp_mfma_ceiling(None, fake(), 1 << 20, 0, byref(flops)) == B.EINVAL
+    assert L.moepp_mfma_ceiling(None, fake(), 1 << 20, 100, None) == B.EINVAL
+    assert L.moepp_mfma_ceiling(None, fake(), 1024, 100, byref(flops)) == B.ENOMEM
