@@ -62,6 +62,16 @@ struct Geo {
     static constexpr int CA = BM * CPR / NT, CB = BN * CPR / NT;   // loads per thread and tile
     static constexpr int STAGE = (BM + BN) * RB;
     static constexpr int KS = BK / 16;                 // MFMA K steps per stage
+    static constexpr int LPT = CA + CB;                // wave-wide loads per thread and tile
+    // Load q of a tile is issued after MFMA number load_pos(q) of the
+    // KS*NB*MB that a wave runs per tile: evenly spread.
+    __host__ __device__ static constexpr int load_pos(int q) { return ((2 * q + 1) * KS * MB * NB) / (2 * LPT); }
+    // How many of them come before the barrier that precedes the last K step.
+    __host__ __device__ static constexpr int loads_before_barrier() {
+        int n = 0;
+        for (int q = 0; q < LPT; ++q) n += load_pos(q) < (KS - 1) * MB * NB ? 1 : 0;
+        return n;
+    }
     static_assert(TM % 32 == 0 && TN % 64 == 0, "wave tile");
     static_assert((BM * CPR) % NT == 0 && (BN * CPR) % NT == 0 && (NT / CPR) % 16 == 0, "chunks");
     static_assert(BK == 32 || BK == 64, "BK");
@@ -170,17 +180,20 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     const int wave_off = __builtin_amdgcn_readfirstlane(wave) * 1024;   // this wave's 1 KB of each load group
 
     const int KT = a.K / BK;
-    auto issue_tile = [&](int kt, char *__restrict__ stage) {
+    // Load q of the LPT = CA + CB wave-wide loads that make up a tile.
+    auto issue_one = [&](int q, int kt, char *__restrict__ stage) {
         char *sa = stage + wave_off;
         char *sb = sa + BM * RB;
+        if (q < CA)
+            __builtin_amdgcn_global_load_lds((gptr_t)(pa[q] + kt * BK),
+                                             (lptr_t)(sa + q * (NT / CPR) * RB), 16, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds((gptr_t)(pb[q - CA] + kt * BK),
+                                             (lptr_t)(sb + (q - CA) * (NT / CPR) * RB), 16, 0, 0);
+    };
+    auto issue_tile = [&](int kt, char *__restrict__ stage) {
 #pragma unroll
-        for (int i = 0; i < CA; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(pa[i] + kt * BK),
-                                             (lptr_t)(sa + i * (NT / CPR) * RB), 16, 0, 0);
-#pragma unroll
-        for (int i = 0; i < CB; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(pb[i] + kt * BK),
-                                             (lptr_t)(sb + i * (NT / CPR) * RB), 16, 0, 0);
+        for (int q = 0; q < CA + CB; ++q) issue_one(q, kt, stage);
     };
 
     // ---- MFMA operand addressing --------------------------------------------
@@ -216,8 +229,29 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
             for (int i = 0; i < MB; ++i)
                 acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[j][i], 0, 0, 0);
     };
+    // The same step with the loads of tile kt_issue spread between the MFMAs:
+    // load q goes after MFMA number G::load_pos(q) of the tile's KS*NB*MB.  A
+    // burst of loads from all waves at once would fill the address queue of
+    // the CU, and a wave that cannot issue its load cannot issue the MFMAs
+    // behind it either.
+    auto mfma_step_issue = [&](const bf16x8 *fa, const bf16x8 *fb, int ks, int kt_issue,
+                               char *__restrict__ wr) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[j][i], 0, 0, 0);
+#pragma unroll
+                for (int q = 0; q < CA + CB; ++q)
+                    if (G::load_pos(q) == (ks * NB + j) * MB + i) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        issue_one(q, kt_issue, wr);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+            }
+    };
 
-    constexpr int LPT = CA + CB;            // loads per thread and tile
+    constexpr int LPT = G::LPT;
     // prologue: tiles 0 .. NS-2 in flight
 #pragma unroll
     for (int p = 0; p < NS - 1; ++p)
@@ -244,17 +278,24 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks + 1 < KS) {
+                    // The operands of this step were read a whole step ago:
+                    // wait for them here, before the next reads go out, or the
+                    // compiler's own wait (placed after them, and for every
+                    // outstanding LDS access) would sit out their latency too.
+                    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
+                    __builtin_amdgcn_sched_barrier(0);
                     read_frags(cur, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);   // issued ahead of this step's MFMAs
                 } else if constexpr (!LAST) {
                     wait_and_barrier<VM>();   // tile kt+1 landed; my reads of tile kt complete
                     __builtin_amdgcn_sched_barrier(0);
-                    if constexpr (ISSUE) issue_tile(kt_issue, wr);
                     read_frags(nxt, 0, fa[0], fb[0]);
                     // keep these reads ahead of the MFMAs below: they fly while
                     // the matrix cores work on the last step of this tile
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                mfma_step(fa[ks & 1], fb[ks & 1]);
+                if constexpr (ISSUE) mfma_step_issue(fa[ks & 1], fb[ks & 1], ks, kt_issue, wr);
+                else mfma_step(fa[ks & 1], fb[ks & 1]);
             }
         };
         int s_cur = 0, s_nxt = 1, s_wr = NS - 1;
@@ -269,7 +310,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         read_frags(lds, 0, fa[0], fb[0]);
         for (int kt = 0; kt < KT - (NS - 1); ++kt) {
             k_tile(lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, kt + NS - 1,
-                   std::integral_constant<int, (NS - 3) * LPT>{}, yes_t{}, no_t{});
+                   std::integral_constant<int, (NS - 3) * LPT + G::loads_before_barrier()>{}, yes_t{}, no_t{});
             rotate();
         }
         // the last NS-1 tiles: nothing left to issue, fewer loads in flight
