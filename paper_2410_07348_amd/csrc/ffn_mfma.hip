@@ -51,29 +51,25 @@ typedef __attribute__((address_space(3))) void *lptr_t;
 
 // Tile geometry.  BK K-elements per LDS stage; NS stages form a ring, NS - 1
 // tiles are in flight (or being computed) at any time.
-template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_>
+// LW_ of the WM*WN waves issue the tile loads (0: all of them).
+template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int LW_ = 0>
 struct Geo {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
     static constexpr int NT = WM * WN * kWave;         // threads
+    static constexpr int LW = LW_ ? LW_ : WM * WN;     // waves that issue the tile loads
+    static constexpr int NL = LW * kWave;              // ... and their threads
     static constexpr int RB = BK * 2;                  // bytes per tile row
     static constexpr int CPR = RB / 16;                // 16-byte slots per tile row
     static constexpr int TM = BM / WM, TN = BN / WN;   // wave tile
     static constexpr int MB = TM / 32, NB = TN / 32;   // 32x32 MFMA blocks per wave
-    static constexpr int CA = BM * CPR / NT, CB = BN * CPR / NT;   // loads per thread and tile
+    static constexpr int CA = BM * CPR / NL, CB = BN * CPR / NL;   // loads per loading thread and tile
     static constexpr int STAGE = (BM + BN) * RB;
     static constexpr int KS = BK / 16;                 // MFMA K steps per stage
     static constexpr int LPT = CA + CB;                // wave-wide loads per thread and tile
-    // Load q of a tile is issued after MFMA number load_pos(q) of the
-    // KS*NB*MB that a wave runs per tile: evenly spread.
-    __host__ __device__ static constexpr int load_pos(int q) { return ((2 * q + 1) * KS * MB * NB) / (2 * LPT); }
-    // How many of them come before the barrier that precedes the last K step.
-    __host__ __device__ static constexpr int loads_before_barrier() {
-        int n = 0;
-        for (int q = 0; q < LPT; ++q) n += load_pos(q) < (KS - 1) * MB * NB ? 1 : 0;
-        return n;
-    }
+    static constexpr int LPS = LPT / KS;               // tile loads per loading thread and K step
+    static_assert(LPT % KS == 0, "tile loads per K step");
     static_assert(TM % 32 == 0 && TN % 64 == 0, "wave tile");
-    static_assert((BM * CPR) % NT == 0 && (BN * CPR) % NT == 0 && (NT / CPR) % 16 == 0, "chunks");
+    static_assert((BM * CPR) % NL == 0 && (BN * CPR) % NL == 0 && (NL / CPR) % 16 == 0, "chunks");
     static_assert(BK == 32 || BK == 64, "BK");
     // XOR swizzle of the 16-byte slots of a tile row.  The LDS has 64 banks of
     // 4 bytes (256 bytes), and a b128 operand read is served 16 lanes at a
@@ -97,7 +93,7 @@ __device__ inline void wait_and_barrier() {
 
 template <class G, bool SWIGLU>
 __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
-    constexpr int BM = G::BM, BN = G::BN, WN = G::WN, NT = G::NT, RB = G::RB, CPR = G::CPR;
+    constexpr int BM = G::BM, BN = G::BN, WN = G::WN, NT = G::NT, NL = G::NL, RB = G::RB, CPR = G::CPR;
     constexpr int TM = G::TM, TN = G::TN, MB = G::MB, NB = G::NB, CA = G::CA, CB = G::CB;
     constexpr int STAGE = G::STAGE, NS = G::NS, BK = G::BK, KS = G::KS;
     constexpr int OUT_W = SWIGLU ? BN / 2 : BN;   // output tile width (elements)
@@ -115,9 +111,12 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     // Workgroups are handed to the 8 XCDs round-robin by id, and every XCD has
     // its own L2.  All tiles are put in one linear order in which 32
     // consecutive tiles form a patch of GM m-tiles x GN n-tiles of one expert
-    // (they share GM + GN operand panels instead of 64), and XCD x works
-    // through the x-th eighth of that order: workgroup w is the (w / 8)-th
-    // tile of XCD w % 8.  The order is computed here from the group offsets.
+    // (they share GM + GN operand panels instead of 64): an XCD's 32 CUs work
+    // on one patch at a time out of their L2.  The patches are dealt to the
+    // XCDs round-robin, so at any time the 8 XCDs hold 8 neighbouring patches
+    // (same rows, next columns): what one XCD fetched from HBM the others
+    // find in the memory-side cache.  Workgroup w is tile w / 8 of XCD w % 8.
+    // The order is computed here from the group offsets.
     constexpr int GM = 8, GN = 4, NXCD = 8;
     int e = 0, row0 = 0, row_end = 0, nt = 0;
     {
@@ -125,10 +124,10 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         int total_mt = 0;
         for (int q = 0; q < a.n_ffn; ++q) total_mt += (a.offsets[q + 1] - a.offsets[q] + BM - 1) / BM;
         const int total = total_mt * Nt;
-        const int chunk = (total + NXCD - 1) / NXCD;
+        // XCD x takes patch-sized chunks x, x+8, x+16, ... of the order
         const int j = blockIdx.x / NXCD;
-        int L = (blockIdx.x % NXCD) * chunk + j;        // linear tile index
-        if (j >= chunk || L >= total) return;
+        int L = ((j / (GM * GN)) * NXCD + blockIdx.x % NXCD) * (GM * GN) + j % (GM * GN);
+        if (L >= total) return;
         int mt_e = 0, b = 0;
         for (e = 0; e < a.n_ffn; ++e) {
             b = a.offsets[e];
@@ -154,7 +153,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     const int n0 = nt * BN;
 
     // ---- global -> LDS, written by the load itself ----------------------------
-    // Chunk c = tid + i*NT of a tile: row c/CPR, 16-byte slot c%CPR.  One
+    // Chunk c = tid + i*NL of a tile (tid < NL: the loading waves): row c/CPR, 16-byte slot c%CPR.  One
     // wave-wide load fills 1 KB of consecutive tile rows: lane l lands at
     // base + 16*l.  Slot s of row r holds global chunk s ^ swz(r) of that row,
     // so each lane fetches the global chunk that belongs in its slot.
@@ -165,7 +164,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     const bf16_t *pb[CB];
 #pragma unroll
     for (int i = 0; i < CA; ++i) {
-        int r = row0 + r_thr + i * (NT / CPR);
+        int r = row0 + r_thr + i * (NL / CPR);
         r = r < row_end ? r : row_end - 1;
         const int src = SWIGLU ? a.src_of[r] / a.topk : r;
         pa[i] = a.A + (size_t)src * a.lda + kc * 8;
@@ -173,7 +172,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     const bf16_t *Be = a.B + (size_t)e * a.Nb * a.K;
 #pragma unroll
     for (int i = 0; i < CB; ++i) {
-        int n = n0 + r_thr + i * (NT / CPR);
+        int n = n0 + r_thr + i * (NL / CPR);
         n = n < a.Nb ? n : a.Nb - 1;
         pb[i] = Be + (size_t)n * a.K + kc * 8;
     }
@@ -186,10 +185,10 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         char *sb = sa + BM * RB;
         if (q < CA)
             __builtin_amdgcn_global_load_lds((gptr_t)(pa[q] + kt * BK),
-                                             (lptr_t)(sa + q * (NT / CPR) * RB), 16, 0, 0);
+                                             (lptr_t)(sa + q * (NL / CPR) * RB), 16, 0, 0);
         else
             __builtin_amdgcn_global_load_lds((gptr_t)(pb[q - CA] + kt * BK),
-                                             (lptr_t)(sb + (q - CA) * (NT / CPR) * RB), 16, 0, 0);
+                                             (lptr_t)(sb + (q - CA) * (NL / CPR) * RB), 16, 0, 0);
     };
     auto issue_tile = [&](int kt, char *__restrict__ stage) {
 #pragma unroll
@@ -229,33 +228,49 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
             for (int i = 0; i < MB; ++i)
                 acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[j][i], 0, 0, 0);
     };
-    // The same step with the loads of tile kt_issue spread between the MFMAs:
-    // load q goes after MFMA number G::load_pos(q) of the tile's KS*NB*MB.  A
-    // burst of loads from all waves at once would fill the address queue of
-    // the CU, and a wave that cannot issue its load cannot issue the MFMAs
-    // behind it either.
-    auto mfma_step_issue = [&](const bf16x8 *fa, const bf16x8 *fb, int ks, int kt_issue,
-                               char *__restrict__ wr) {
+    // One K step with its memory operations spread evenly between the MFMAs:
+    // first the operand reads of the NEXT step (from `st`, step `ks_rd`, into
+    // fa_n/fb_n), then N_LOAD of the loads of tile kt_issue.  A wave issues in
+    // order: a burst of reads or loads between two MFMAs leaves the matrix
+    // core idle, a single one does not.
+    auto mfma_step_mem = [&](const bf16x8 *fa, const bf16x8 *fb, int ks, bool do_read,
+                             const char *__restrict__ st, int ks_rd, bf16x8 *fa_n, bf16x8 *fb_n,
+                             auto n_load_c, int kt_issue, char *__restrict__ wr) {
+        constexpr int N_LOAD = decltype(n_load_c)::value;
+        constexpr int N_READ = MB + NB, OPS = N_READ + N_LOAD, SLOTS = MB * NB;
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int i = 0; i < MB; ++i) {
                 acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[j][i], 0, 0, 0);
+                const int idx = j * MB + i;
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int q = 0; q < CA + CB; ++q)
-                    if (G::load_pos(q) == (ks * NB + j) * MB + i) {
-                        __builtin_amdgcn_sched_barrier(0);
-                        issue_one(q, kt_issue, wr);
-                        __builtin_amdgcn_sched_barrier(0);
+                for (int o = 0; o < OPS; ++o) {
+                    if (o * SLOTS / OPS != idx) continue;
+                    if (o >= N_READ) {
+                        issue_one(ks * N_LOAD + o - N_READ, kt_issue, wr);
+                    } else if (do_read) {
+                        // order of first use by the next step: fb[0], fa[0..], fb[1..]
+                        if (o == 0)
+                            fb_n[0] = *reinterpret_cast<const bf16x8 *>(st + b_base + rd_off[ks_rd]);
+                        else if (o <= MB)
+                            fa_n[o - 1] = *reinterpret_cast<const bf16x8 *>(st + a_base + (o - 1) * 32 * RB + rd_off[ks_rd]);
+                        else
+                            fb_n[o - MB] = *reinterpret_cast<const bf16x8 *>(st + b_base + (o - MB) * 32 * RB + rd_off[ks_rd]);
                     }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
     };
 
     constexpr int LPT = G::LPT;
     // prologue: tiles 0 .. NS-2 in flight
+    auto prologue = [&]() {
 #pragma unroll
-    for (int p = 0; p < NS - 1; ++p)
-        if (p < KT) issue_tile(p, lds + p * STAGE);
+        for (int p = 0; p < NS - 1; ++p)
+            if (p < KT) issue_tile(p, lds + p * STAGE);
+    };
 
     if constexpr (NS >= 3) {
         // Ring of NS stages, tile kt in stage kt % NS.  The workgroup barrier
@@ -267,6 +282,12 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         // loop body is branch-free (the last NS-1 tiles are peeled off), which
         // keeps the compiler's wait-count tracking exact.  Needs KT >= NS-1.
         static_assert(KS % 2 == 0, "operand double buffering assumes an even number of K steps");
+        // LOADER: this wave issues tile loads.  With G::LW < WM*WN only the
+        // first LW waves do; the others run the same loop without them (two
+        // copies of the loop, chosen once per wave, each branch-free inside).
+        auto ring = [&](auto loader_c) {
+        constexpr bool LOADER = decltype(loader_c)::value;
+        if constexpr (LOADER) prologue();
         bf16x8 fa[2][MB], fb[2][NB];
         // One tile.  cur / nxt / wr are three different stages (restrict): the
         // loads that refill wr never make the operand reads wait.  VM = loads of
@@ -275,27 +296,21 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
                           char *__restrict__ wr, int kt_issue, auto vm_c, auto issue_c, auto last_c) {
             constexpr int VM = decltype(vm_c)::value;
             constexpr bool ISSUE = decltype(issue_c)::value, LAST = decltype(last_c)::value;
+            typedef std::integral_constant<int, ISSUE && LOADER ? G::LPS : 0> n_load_t;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks + 1 < KS) {
-                    // The operands of this step were read a whole step ago:
-                    // wait for them here, before the next reads go out, or the
-                    // compiler's own wait (placed after them, and for every
-                    // outstanding LDS access) would sit out their latency too.
+                    // operands of this step: read during the previous step
                     __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
                     __builtin_amdgcn_sched_barrier(0);
-                    read_frags(cur, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
-                    __builtin_amdgcn_sched_barrier(0);   // issued ahead of this step's MFMAs
-                } else if constexpr (!LAST) {
-                    wait_and_barrier<VM>();   // tile kt+1 landed; my reads of tile kt complete
+                    mfma_step_mem(fa[ks & 1], fb[ks & 1], ks, true, cur, ks + 1, fa[(ks + 1) & 1],
+                                  fb[(ks + 1) & 1], n_load_t{}, kt_issue, wr);
+                } else {
+                    if constexpr (!LAST) wait_and_barrier<VM>();   // tile kt+1 landed; my reads of tile kt complete
+                    else __builtin_amdgcn_s_waitcnt(0xC07F);
                     __builtin_amdgcn_sched_barrier(0);
-                    read_frags(nxt, 0, fa[0], fb[0]);
-                    // keep these reads ahead of the MFMAs below: they fly while
-                    // the matrix cores work on the last step of this tile
-                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_step_mem(fa[ks & 1], fb[ks & 1], ks, !LAST, nxt, 0, fa[0], fb[0], n_load_t{}, kt_issue, wr);
                 }
-                if constexpr (ISSUE) mfma_step_issue(fa[ks & 1], fb[ks & 1], ks, kt_issue, wr);
-                else mfma_step(fa[ks & 1], fb[ks & 1]);
             }
         };
         int s_cur = 0, s_nxt = 1, s_wr = NS - 1;
@@ -310,7 +325,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         read_frags(lds, 0, fa[0], fb[0]);
         for (int kt = 0; kt < KT - (NS - 1); ++kt) {
             k_tile(lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, kt + NS - 1,
-                   std::integral_constant<int, (NS - 3) * LPT + G::loads_before_barrier()>{}, yes_t{}, no_t{});
+                   std::integral_constant<int, (NS - 3) * LPT + (KS - 1) * G::LPS>{}, yes_t{}, no_t{});
             rotate();
         }
         // the last NS-1 tiles: nothing left to issue, fewer loads in flight
@@ -329,7 +344,16 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         tail(std::integral_constant<int, 2>{});
         tail(std::integral_constant<int, 3>{});
         static_assert(NS <= 5, "tail unrolling covers NS - 1 <= 4 tiles");
+        };   // ring
+        if constexpr (G::LW == G::WM * WN) {
+            ring(std::true_type{});
+        } else {
+            if (__builtin_amdgcn_readfirstlane(wave) < G::LW) ring(std::true_type{});
+            else ring(std::false_type{});
+        }
     } else {
+        static_assert(G::LW == G::WM * WN, "the two-stage path loads with every wave");
+        prologue();
         // Two stages: refill the stage that was computed last with the next
         // tile, then run the MFMAs of this one.  `rd` and `wr` never overlap
         // (restrict), so the operand reads are not made to wait on those loads.
@@ -440,7 +464,8 @@ static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
     a.n_ntiles = (a.Nb + BN - 1) / BN;
     const long long rows = (long long)f.d.T * f.d.k;
     const long long max_mtiles = (rows + BM - 1) / BM + f.d.n_ffn;   // upper bound of sum ceil(count_e/BM)
-    const long long blocks = (max_mtiles * a.n_ntiles + 7) / 8 * 8;   // whole rounds over the 8 XCDs
+    const long long rnd = 8 * 8 * 4;   // whole rounds of one patch (GM x GN tiles) per XCD
+    const long long blocks = (max_mtiles * a.n_ntiles + rnd - 1) / rnd * rnd;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     dim3 grid((unsigned)blocks), block(G::NT);
     if (which == 0)
@@ -452,9 +477,12 @@ static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
 
 hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
     if (f.d.T == 0 || f.d.n_ffn == 0) return hipSuccess;
-    // Default: 256x256 tile, 32-deep K stages in a ring of 5 (the whole 160 KB
-    // of LDS), which needs at least 4 K tiles; shorter reductions use two
-    // 64-deep stages.  MOEPP_GEMM_CFG (1..3) selects other geometries, for tuning.
+    // Default: 256x256 tile, 8 waves of which the first 4 issue the tile loads,
+    // 32-deep K stages in a ring of 5 (the whole 160 KB of LDS), which needs
+    // at least 4 K tiles; shorter reductions use two 64-deep stages.
+    // MOEPP_GEMM_CFG selects other geometries, for tuning: 1 = 4 waves with
+    // 128x128 wave tiles, 2 = ring of 3, 3 = two 64-deep stages, 5 = every
+    // wave loads.
     const char *v = getenv("MOEPP_GEMM_CFG");
     int cfg = v ? atoi(v) : 0;
     const int K = which == 0 ? f.d.D : f.d.F;
@@ -463,7 +491,8 @@ hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
         case 1: return launch_cfg<Geo<256, 256, 2, 2, 32, 5>>(f, which, s);
         case 2: return launch_cfg<Geo<256, 256, 2, 4, 32, 3>>(f, which, s);
         case 3: return launch_cfg<Geo<256, 256, 2, 4, 64, 2>>(f, which, s);
-        default: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);
+        case 5: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);
+        default: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4>>(f, which, s);
     }
 }
 
