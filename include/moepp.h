@@ -102,7 +102,10 @@ moepp_status moepp_destroy(moepp_ctx *ctx);
  * kernels read (weights are static across forward calls, so this is not part
  * of the forward pass): W1 and W3 of an expert are interleaved in blocks of
  * 32 rows ([32 rows of W1][32 rows of W3]...) so that one output tile holds
- * silu's argument and its multiplier for the same columns; W2 is copied.
+ * silu's argument and its multiplier for the same columns, and every matrix
+ * is stored in slabs of 32 columns (slab s = columns 32s..32s+31 of every
+ * row, rows consecutive), so that what a GEMM tile reads per K step is one
+ * consecutive piece of memory.  The packed layout is private to the library.
  * `packed` must hold moepp_packed_bytes(desc) bytes (ENOMEM otherwise).
  */
 moepp_status moepp_pack_experts(moepp_ctx *ctx, void *stream,
@@ -192,8 +195,11 @@ moepp_status moepp_get_routing(moepp_ctx *ctx, const int32_t **topk_idx,
 
 /*
  * Device pointers to intermediates of the last call: alpha1 [T,n_const]
- * float32 (a1 of Eq.5), h [R,F] act (SwiGLU intermediate, row order of
- * src_of), yffn [R,D] act (FFN expert outputs).  Any pointer may be NULL.
+ * float32 (a1 of Eq.5), h (SwiGLU intermediate, rows in the order of src_of)
+ * and yffn [R,D] act row-major (FFN expert outputs).  h is stored in slabs
+ * of 32 columns over T_max*k rows: element (r, f) is at
+ * (f/32)*(T_max*k)*32 + r*w + f%32 with w = min(32, F - 32*(f/32)); rows
+ * r < R hold data.  Any pointer may be NULL.
  */
 moepp_status moepp_get_intermediates(moepp_ctx *ctx, const float **alpha1,
                                      const void **h, const void **yffn);

@@ -272,6 +272,12 @@ class Layer:
             R = int(self.get_routing()["offsets"][-1].item()) if d.n_ffn else 0
         out = {"alpha1": self._view(p[0].value, T * d.n_const, t.float32).view(T, d.n_const)}
         if d.n_ffn:
-            out["h"] = self._view(p[1].value, R * d.F, self.act_dtype).view(R, d.F)
+            # h is stored in slabs of 32 columns over T_max*k rows: gather it to [R,F]
+            slots, cols = d.T_max * d.k, []
+            raw = self._view(p[1].value, slots * d.F, self.act_dtype)
+            for s0 in range(0, d.F, 32):
+                w = min(32, d.F - s0)
+                cols.append(raw[s0 * slots: s0 * slots + slots * w].view(slots, w)[:R])
+            out["h"] = t.cat(cols, dim=1)
             out["yffn"] = self._view(p[2].value, R * d.D, self.act_dtype).view(R, d.D)
         return out

@@ -32,6 +32,21 @@ __host__ __device__ inline int packed_row(int f, int up, int F) {
     return b * 2 * kPackBlk + up * bs + (f - b * kPackBlk);
 }
 
+// K-slab-major storage of a matrix [N rows, K columns]: slab s holds columns
+// [s*kSlab, (s+1)*kSlab) of every row, rows consecutive, so that the part of
+// the matrix a GEMM tile needs for one K step (some consecutive rows x one
+// slab) is one consecutive piece of memory.  The last slab is narrower when
+// K % kSlab != 0.  Used for the packed expert weights and for h.
+constexpr int kSlab = 32;
+__host__ __device__ inline int slab_width(int s, int K) {
+    const int rem = K - s * kSlab;
+    return rem < kSlab ? rem : kSlab;
+}
+// element offset of (row n, first column of slab s)
+__host__ __device__ inline size_t slab_row(int n, int s, int N, int K) {
+    return (size_t)s * N * kSlab + (size_t)n * slab_width(s, K);
+}
+
 struct Dims {
     int T, D, F;
     int n_ffn, n_zero, n_copy, n_const, N;
@@ -49,7 +64,7 @@ struct Workspace {
     int32_t *src_of;     // [T_max*k]
     int32_t *chunk_hist; // [n_chunks*N]
     int32_t *chunk_base; // [n_chunks*N]
-    void *h;             // [T_max*k, F] act
+    void *h;             // [T_max*k, F] act, K-slab-major
     void *yffn;          // [T_max*k, D] act
     void *wsplit;        // router_split_bytes(D, N + 2 n_const)
 };
@@ -68,12 +83,13 @@ struct RouterArgs {
 struct FfnArgs {
     Dims d;
     const void *x;        // [T,D]
-    const void *w13;      // packed [n_ffn][2F][D]
-    const void *w2;       // [n_ffn][D][F]
+    const void *w13;      // packed: [n_ffn] matrices [2F, D], K-slab-major, rows in packed_row order
+    const void *w2;       // packed: [n_ffn] matrices [D, F], K-slab-major
     const int32_t *offsets;
     const int32_t *src_of;
-    void *h;              // [R,F]
-    void *yffn;           // [R,D]
+    void *h;              // [h_rows, F] K-slab-major; rows < R are written
+    void *yffn;           // [R,D] row-major
+    int h_rows;           // T_max * k
 };
 
 struct CombineArgs {

@@ -27,19 +27,23 @@ __global__ __launch_bounds__(256) void k_ffn1_generic(FfnArgs a) {
     const int t = a.src_of[r] / a.d.k;
     const AT *x = static_cast<const AT *>(a.x) + (size_t)t * D;
     const AT *W = static_cast<const AT *>(a.w13) + (size_t)e * 2 * F * D;
-    const AT *wg = W + (size_t)packed_row(f, 0, F) * D;
-    const AT *wu = W + (size_t)packed_row(f, 1, F) * D;
+    const int rg = packed_row(f, 0, F), ru = packed_row(f, 1, F);
     constexpr int V = ActVec<AT>::N;
     float g = 0.f, u = 0.f;
-    for (int d = 0; d < D; d += V) {
-        ActVec<AT> xv = load_vec(x + d), gv = load_vec(wg + d), uv = load_vec(wu + d);
+    for (int s = 0; s * kSlab < D; ++s) {          // the packed weights are K-slab-major
+        const AT *wg = W + slab_row(rg, s, 2 * F, D);
+        const AT *wu = W + slab_row(ru, s, 2 * F, D);
+        const int kw = slab_width(s, D);
+        for (int d = 0; d < kw; d += V) {
+            ActVec<AT> xv = load_vec(x + s * kSlab + d), gv = load_vec(wg + d), uv = load_vec(wu + d);
 #pragma unroll
-        for (int i = 0; i < V; ++i) {
-            g = fmaf(gv.get(i), xv.get(i), g);
-            u = fmaf(uv.get(i), xv.get(i), u);
+            for (int i = 0; i < V; ++i) {
+                g = fmaf(gv.get(i), xv.get(i), g);
+                u = fmaf(uv.get(i), xv.get(i), u);
+            }
         }
     }
-    static_cast<AT *>(a.h)[(size_t)r * F + f] = (AT)(silu_f(g) * u);
+    static_cast<AT *>(a.h)[slab_row(r, f / kSlab, a.h_rows, F) + f % kSlab] = (AT)(silu_f(g) * u);
 }
 
 // yffn[r,d] = W2_e[d,:] h[r,:]
@@ -51,14 +55,19 @@ __global__ __launch_bounds__(256) void k_ffn2_generic(FfnArgs a) {
     if (r >= R || dd >= a.d.D) return;
     const int D = a.d.D, F = a.d.F;
     const int e = expert_of_row(a.offsets, a.d.n_ffn, r);
-    const AT *h = static_cast<const AT *>(a.h) + (size_t)r * F;
-    const AT *w = static_cast<const AT *>(a.w2) + ((size_t)e * D + dd) * F;
+    const AT *hb = static_cast<const AT *>(a.h);
+    const AT *wb = static_cast<const AT *>(a.w2) + (size_t)e * D * F;
     constexpr int V = ActVec<AT>::N;
     float acc = 0.f;
-    for (int f = 0; f < F; f += V) {
-        ActVec<AT> hv = load_vec(h + f), wv = load_vec(w + f);
+    for (int s = 0; s * kSlab < F; ++s) {          // h and the packed weights are K-slab-major
+        const AT *h = hb + slab_row(r, s, a.h_rows, F);
+        const AT *w = wb + slab_row(dd, s, D, F);
+        const int kw = slab_width(s, F);
+        for (int f = 0; f < kw; f += V) {
+            ActVec<AT> hv = load_vec(h + f), wv = load_vec(w + f);
 #pragma unroll
-        for (int i = 0; i < V; ++i) acc = fmaf(wv.get(i), hv.get(i), acc);
+            for (int i = 0; i < V; ++i) acc = fmaf(wv.get(i), hv.get(i), acc);
+        }
     }
     static_cast<AT *>(a.yffn)[(size_t)r * D + dd] = (AT)acc;
 }

@@ -31,12 +31,13 @@
 namespace moepp {
 
 struct GemmArgs {
-    const bf16_t *A;         // GEMM1: x [T, lda]; GEMM2: h [R, lda]
-    const bf16_t *B;         // [n_ffn][Nb][K]
-    bf16_t *C;               // [R, ldc]
+    const bf16_t *A;         // GEMM1: x [T, ld] row-major; GEMM2: h, K-slab-major over h_rows rows
+    const bf16_t *B;         // [n_ffn] matrices [Nb, K], K-slab-major
+    bf16_t *C;               // GEMM1: h, K-slab-major over h_rows rows; GEMM2: yffn [R, ld] row-major
     const int32_t *offsets;  // [n_ffn + 1]
     const int32_t *src_of;   // GEMM1 only
-    int lda, ldc;
+    int ld;                  // row length of the row-major operand (x or yffn)
+    int h_rows;              // rows of the slab-major h buffer
     int K;                   // reduction length (multiple of 64)
     int Nb;                  // rows of B per expert (2F or D)
     int Nc;                  // columns of C (F or D)
@@ -167,27 +168,32 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         int r = row0 + r_thr + i * (NL / CPR);
         r = r < row_end ? r : row_end - 1;
         const int src = SWIGLU ? a.src_of[r] / a.topk : r;
-        pa[i] = a.A + (size_t)src * a.lda + kc * 8;
+        // chunk kc of the tile: slab kc/4 of the tile's K range, 16-byte piece kc%4 of the slab row
+        pa[i] = SWIGLU ? a.A + (size_t)src * a.ld + kc * 8
+                       : a.A + (size_t)(kc / 4) * a.h_rows * kSlab + (size_t)src * kSlab + (kc % 4) * 8;
     }
     const bf16_t *Be = a.B + (size_t)e * a.Nb * a.K;
 #pragma unroll
     for (int i = 0; i < CB; ++i) {
         int n = n0 + r_thr + i * (NL / CPR);
         n = n < a.Nb ? n : a.Nb - 1;
-        pb[i] = Be + (size_t)n * a.K + kc * 8;
+        pb[i] = Be + (size_t)(kc / 4) * a.Nb * kSlab + (size_t)n * kSlab + (kc % 4) * 8;
     }
     const int wave_off = __builtin_amdgcn_readfirstlane(wave) * 1024;   // this wave's 1 KB of each load group
 
     const int KT = a.K / BK;
+    // elements from one K tile to the next
+    const size_t a_kstep = SWIGLU ? (size_t)BK : (size_t)(BK / kSlab) * a.h_rows * kSlab;
+    const size_t b_kstep = (size_t)(BK / kSlab) * a.Nb * kSlab;
     // Load q of the LPT = CA + CB wave-wide loads that make up a tile.
     auto issue_one = [&](int q, int kt, char *__restrict__ stage) {
         char *sa = stage + wave_off;
         char *sb = sa + BM * RB;
         if (q < CA)
-            __builtin_amdgcn_global_load_lds((gptr_t)(pa[q] + kt * BK),
+            __builtin_amdgcn_global_load_lds((gptr_t)(pa[q] + kt * a_kstep),
                                              (lptr_t)(sa + q * (NL / CPR) * RB), 16, 0, 0);
         else
-            __builtin_amdgcn_global_load_lds((gptr_t)(pb[q - CA] + kt * BK),
+            __builtin_amdgcn_global_load_lds((gptr_t)(pb[q - CA] + kt * b_kstep),
                                              (lptr_t)(sb + (q - CA) * (NL / CPR) * RB), 16, 0, 0);
     };
     auto issue_tile = [&](int kt, char *__restrict__ stage) {
@@ -423,12 +429,26 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     __syncthreads();
     constexpr int OCPR = OUT_W / 8;                // 16-byte chunks per output row
     const int c_col0 = SWIGLU ? n0 / 2 : n0;
-    for (int c = tid; c < BM * OCPR; c += NT) {
-        const int m = c / OCPR, cc = c % OCPR;
-        const int row = row0 + m, col = c_col0 + cc * 8;
-        if (row < row_end && col < a.Nc)
-            *reinterpret_cast<bf16x8 *>(a.C + (size_t)row * a.ldc + col) =
-                *reinterpret_cast<const bf16x8 *>(lds + m * OUT_STRIDE + cc * 16);
+    if constexpr (SWIGLU) {
+        // h is K-slab-major: the tile is OUT_W/32 slabs of BM rows x 64 bytes,
+        // each consecutive in memory; consecutive threads take consecutive
+        // 16-byte pieces of a slab.
+        for (int c = tid; c < BM * OCPR; c += NT) {
+            const int sl = c / (BM * 4), m = (c / 4) % BM, q = c % 4;
+            const int row = row0 + m, col = c_col0 + sl * kSlab + q * 8;
+            if (row < row_end && col < a.Nc)
+                *reinterpret_cast<bf16x8 *>(a.C + (size_t)(col / kSlab) * a.h_rows * kSlab +
+                                            (size_t)row * kSlab + q * 8) =
+                    *reinterpret_cast<const bf16x8 *>(lds + m * OUT_STRIDE + (sl * 4 + q) * 16);
+        }
+    } else {
+        for (int c = tid; c < BM * OCPR; c += NT) {
+            const int m = c / OCPR, cc = c % OCPR;
+            const int row = row0 + m, col = c_col0 + cc * 8;
+            if (row < row_end && col < a.Nc)
+                *reinterpret_cast<bf16x8 *>(a.C + (size_t)row * a.ld + col) =
+                    *reinterpret_cast<const bf16x8 *>(lds + m * OUT_STRIDE + cc * 16);
+        }
     }
 }
 
@@ -441,23 +461,22 @@ static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
     a.src_of = f.src_of;
     a.n_ffn = f.d.n_ffn;
     a.topk = f.d.k;
+    a.h_rows = f.h_rows;
     if (which == 0) {
         a.A = (const bf16_t *)f.x;
-        a.lda = f.d.D;
+        a.ld = f.d.D;
         a.B = (const bf16_t *)f.w13;
         a.K = f.d.D;
         a.Nb = 2 * f.d.F;
         a.C = (bf16_t *)f.h;
-        a.ldc = f.d.F;
         a.Nc = f.d.F;
     } else {
         a.A = (const bf16_t *)f.h;
-        a.lda = f.d.F;
         a.B = (const bf16_t *)f.w2;
         a.K = f.d.F;
         a.Nb = f.d.D;
         a.C = (bf16_t *)f.yffn;
-        a.ldc = f.d.D;
+        a.ld = f.d.D;
         a.Nc = f.d.D;
     }
     constexpr int BM = G::BM, BN = G::BN;

@@ -214,6 +214,7 @@ moepp_status do_ffn(moepp_ctx *c, hipStream_t s, int T, const void *x, const voi
     a.src_of = c->ws.src_of;
     a.h = c->ws.h;
     a.yffn = c->ws.yffn;
+    a.h_rows = c->desc.T_max * c->desc.k;
     const bool bf = c->desc.act == MOEPP_BF16;
     hipError_t e;
     {
