@@ -103,9 +103,10 @@ moepp_status moepp_destroy(moepp_ctx *ctx);
  * of the forward pass): W1 and W3 of an expert are interleaved in blocks of
  * 32 rows ([32 rows of W1][32 rows of W3]...) so that one output tile holds
  * silu's argument and its multiplier for the same columns, and every matrix
- * is stored in slabs of 32 columns (slab s = columns 32s..32s+31 of every
- * row, rows consecutive), so that what a GEMM tile reads per K step is one
- * consecutive piece of memory.  The packed layout is private to the library.
+ * is stored in panels of 256 rows, each panel in slabs of 32 columns (slab s
+ * = columns 32s..32s+31 of the panel's rows, rows consecutive), so that what
+ * a GEMM tile reads of a weight matrix is one consecutive run of memory, in
+ * the order it is read.  The packed layout is private to the library.
  * `packed` must hold moepp_packed_bytes(desc) bytes (ENOMEM otherwise).
  */
 moepp_status moepp_pack_experts(moepp_ctx *ctx, void *stream,

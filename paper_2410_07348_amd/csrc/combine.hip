@@ -106,19 +106,19 @@ __global__ __launch_bounds__(256) void k_pack(Dims d, const AT *w1, const AT *w3
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (size_t)gridDim.x * blockDim.x) {
         const size_t e = i / per, v = i % per;
-        {   // W1 / W3 row f, columns dv..: packed rows of the [2F, D] matrix, K-slab-major
+        {   // W1 / W3 row f, columns dv..: packed rows of the [2F, D] matrix, in panels
             const int f = (int)(v / (d.D / V));
             const int dv = (int)(v % (d.D / V)) * V;
             AT *dst = w13 + e * 2 * d.F * d.D;
             const int sl = dv / kSlab, in = dv % kSlab;
-            store_vec(dst + slab_row(packed_row(f, 0, d.F), sl, 2 * d.F, d.D) + in, load_vec(w1 + i * V));
-            store_vec(dst + slab_row(packed_row(f, 1, d.F), sl, 2 * d.F, d.D) + in, load_vec(w3 + i * V));
+            store_vec(dst + panel_row(packed_row(f, 0, d.F), sl, 2 * d.F, d.D) + in, load_vec(w1 + i * V));
+            store_vec(dst + panel_row(packed_row(f, 1, d.F), sl, 2 * d.F, d.D) + in, load_vec(w3 + i * V));
         }
-        {   // W2 row dd, columns fv..: the [D, F] matrix, K-slab-major
+        {   // W2 row dd, columns fv..: the [D, F] matrix, in panels
             const int dd = (int)(v / (d.F / V));
             const int fv = (int)(v % (d.F / V)) * V;
             AT *dst = w2o + e * d.D * d.F;
-            store_vec(dst + slab_row(dd, fv / kSlab, d.D, d.F) + fv % kSlab, load_vec(w2 + i * V));
+            store_vec(dst + panel_row(dd, fv / kSlab, d.D, d.F) + fv % kSlab, load_vec(w2 + i * V));
         }
     }
 }

@@ -36,7 +36,7 @@ __host__ __device__ inline int packed_row(int f, int up, int F) {
 // [s*kSlab, (s+1)*kSlab) of every row, rows consecutive, so that the part of
 // the matrix a GEMM tile needs for one K step (some consecutive rows x one
 // slab) is one consecutive piece of memory.  The last slab is narrower when
-// K % kSlab != 0.  Used for the packed expert weights and for h.
+// K % kSlab != 0.  Used for h.
 constexpr int kSlab = 32;
 __host__ __device__ inline int slab_width(int s, int K) {
     const int rem = K - s * kSlab;
@@ -45,6 +45,19 @@ __host__ __device__ inline int slab_width(int s, int K) {
 // element offset of (row n, first column of slab s)
 __host__ __device__ inline size_t slab_row(int n, int s, int N, int K) {
     return (size_t)s * N * kSlab + (size_t)n * slab_width(s, K);
+}
+
+// The packed expert weight matrices [N rows, K columns] are stored in panels
+// of kPanel rows (the GEMM's tile height), each panel K-slab-major: all that
+// one GEMM tile reads of the matrix, in the order it reads it, is one
+// consecutive run of memory.  The last panel has fewer rows when
+// N % kPanel != 0.  Element offset of (row n, first column of slab s):
+constexpr int kPanel = 256;
+__host__ __device__ inline size_t panel_row(int n, int s, int N, int K) {
+    const int p = n / kPanel;
+    const int rem = N - p * kPanel;
+    const int rows = rem < kPanel ? rem : kPanel;
+    return (size_t)p * kPanel * K + slab_row(n - p * kPanel, s, rows, K);
 }
 
 struct Dims {
@@ -83,8 +96,8 @@ struct RouterArgs {
 struct FfnArgs {
     Dims d;
     const void *x;        // [T,D]
-    const void *w13;      // packed: [n_ffn] matrices [2F, D], K-slab-major, rows in packed_row order
-    const void *w2;       // packed: [n_ffn] matrices [D, F], K-slab-major
+    const void *w13;      // packed: [n_ffn] matrices [2F, D] in panels (panel_row), rows in packed_row order
+    const void *w2;       // packed: [n_ffn] matrices [D, F] in panels (panel_row)
     const int32_t *offsets;
     const int32_t *src_of;
     void *h;              // [h_rows, F] K-slab-major; rows < R are written

@@ -30,9 +30,9 @@ __global__ __launch_bounds__(256) void k_ffn1_generic(FfnArgs a) {
     const int rg = packed_row(f, 0, F), ru = packed_row(f, 1, F);
     constexpr int V = ActVec<AT>::N;
     float g = 0.f, u = 0.f;
-    for (int s = 0; s * kSlab < D; ++s) {          // the packed weights are K-slab-major
-        const AT *wg = W + slab_row(rg, s, 2 * F, D);
-        const AT *wu = W + slab_row(ru, s, 2 * F, D);
+    for (int s = 0; s * kSlab < D; ++s) {          // the packed weights: panels of K slabs
+        const AT *wg = W + panel_row(rg, s, 2 * F, D);
+        const AT *wu = W + panel_row(ru, s, 2 * F, D);
         const int kw = slab_width(s, D);
         for (int d = 0; d < kw; d += V) {
             ActVec<AT> xv = load_vec(x + s * kSlab + d), gv = load_vec(wg + d), uv = load_vec(wu + d);
@@ -59,9 +59,9 @@ __global__ __launch_bounds__(256) void k_ffn2_generic(FfnArgs a) {
     const AT *wb = static_cast<const AT *>(a.w2) + (size_t)e * D * F;
     constexpr int V = ActVec<AT>::N;
     float acc = 0.f;
-    for (int s = 0; s * kSlab < F; ++s) {          // h and the packed weights are K-slab-major
+    for (int s = 0; s * kSlab < F; ++s) {          // h is K-slab-major, the packed weights are panels of K slabs
         const AT *h = hb + slab_row(r, s, a.h_rows, F);
-        const AT *w = wb + slab_row(dd, s, D, F);
+        const AT *w = wb + panel_row(dd, s, D, F);
         const int kw = slab_width(s, F);
         for (int f = 0; f < kw; f += V) {
             ActVec<AT> hv = load_vec(h + f), wv = load_vec(w + f);

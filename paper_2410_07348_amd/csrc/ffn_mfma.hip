@@ -32,7 +32,7 @@ namespace moepp {
 
 struct GemmArgs {
     const bf16_t *A;         // GEMM1: x [T, ld] row-major; GEMM2: h, K-slab-major over h_rows rows
-    const bf16_t *B;         // [n_ffn] matrices [Nb, K], K-slab-major
+    const bf16_t *B;         // [n_ffn] matrices [Nb, K] in panels of K slabs (panel_row)
     bf16_t *C;               // GEMM1: h, K-slab-major over h_rows rows; GEMM2: yffn [R, ld] row-major
     const int32_t *offsets;  // [n_ffn + 1]
     const int32_t *src_of;   // GEMM1 only
@@ -177,14 +177,16 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     for (int i = 0; i < CB; ++i) {
         int n = n0 + r_thr + i * (NL / CPR);
         n = n < a.Nb ? n : a.Nb - 1;
-        pb[i] = Be + (size_t)(kc / 4) * a.Nb * kSlab + (size_t)n * kSlab + (kc % 4) * 8;
+        pb[i] = Be + panel_row(n, kc / 4, a.Nb, a.K) + (kc % 4) * 8;
     }
     const int wave_off = __builtin_amdgcn_readfirstlane(wave) * 1024;   // this wave's 1 KB of each load group
 
     const int KT = a.K / BK;
     // elements from one K tile to the next
     const size_t a_kstep = SWIGLU ? (size_t)BK : (size_t)(BK / kSlab) * a.h_rows * kSlab;
-    const size_t b_kstep = (size_t)(BK / kSlab) * a.Nb * kSlab;
+    static_assert(BN == kPanel, "one tile of B rows is one panel of the packed weights");
+    const int b_rows = a.Nb - n0 < BN ? a.Nb - n0 : BN;            // rows of this tile's panel
+    const size_t b_kstep = (size_t)(BK / kSlab) * b_rows * kSlab;
     // Load q of the LPT = CA + CB wave-wide loads that make up a tile.
     auto issue_one = [&](int q, int kt, char *__restrict__ stage) {
         char *sa = stage + wave_off;
