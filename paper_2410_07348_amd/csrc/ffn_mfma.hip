@@ -122,21 +122,32 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     int e = 0, row0 = 0, row_end = 0, nt = 0;
     {
         const int Nt = a.n_ntiles;
-        int total_mt = 0;
-        for (int q = 0; q < a.n_ffn; ++q) total_mt += (a.offsets[q + 1] - a.offsets[q] + BM - 1) / BM;
-        const int total = total_mt * Nt;
+        // Lane q holds group q: one vector load of the offsets, a wave-wide
+        // prefix sum of the tile counts, a ballot to find the group of tile L
+        // (a scalar loop over the groups costs a dependent memory round trip
+        // per group: measured 3.9 us per workgroup with 16 groups).
+        const int q = lane < a.n_ffn ? lane : a.n_ffn;
+        const int o_lo = a.offsets[q];
+        const int o_hi = a.offsets[q < a.n_ffn ? q + 1 : q];
+        const int mt_q = (o_hi - o_lo + BM - 1) / BM;          // 0 for lanes past the last group
+        int incl = mt_q * Nt;                                   // inclusive prefix sum over lanes
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int up = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += up;
+        }
+        const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
         // XCD x takes patch-sized chunks x, x+8, x+16, ... of the order
         const int j = blockIdx.x / NXCD;
         int L = ((j / (GM * GN)) * NXCD + blockIdx.x % NXCD) * (GM * GN) + j % (GM * GN);
         if (L >= total) return;
-        int mt_e = 0, b = 0;
-        for (e = 0; e < a.n_ffn; ++e) {
-            b = a.offsets[e];
-            row_end = a.offsets[e + 1];
-            mt_e = (row_end - b + BM - 1) / BM;
-            if (L < mt_e * Nt) break;
-            L -= mt_e * Nt;
-        }
+        const unsigned long long past = __ballot(incl > L);     // lanes whose groups end after tile L
+        e = __builtin_ctzll(past);                              // L < total, so some lane has incl > L
+        // (e is the same in every lane: these are scalar reads of lane e)
+        L -= __builtin_amdgcn_readlane(incl - mt_q * Nt, e);
+        const int b = __builtin_amdgcn_readlane(o_lo, e);
+        row_end = __builtin_amdgcn_readlane(o_hi, e);
+        const int mt_e = __builtin_amdgcn_readlane(mt_q, e);
         // inside expert e: m-groups of GM m-tiles, n-groups of GN n-tiles, m fastest
         const int n_g = (mt_e + GM - 1) / GM;
         int g = L / (GM * Nt);
