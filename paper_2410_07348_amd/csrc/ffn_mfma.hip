@@ -307,6 +307,8 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         auto ring = [&](auto loader_c) {
         constexpr bool LOADER = decltype(loader_c)::value;
         if constexpr (LOADER) prologue();
+        // the loading waves win instruction arbitration over the others (+1 %, measured)
+        if constexpr (G::LW != G::WM * WN) __builtin_amdgcn_s_setprio(LOADER ? 2 : 0);
         bf16x8 fa[2][MB], fb[2][NB];
         // One tile.  cur / nxt / wr are three different stages (restrict): the
         // loads that refill wr never make the operand reads wait.  VM = loads of
@@ -369,6 +371,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         } else {
             if (__builtin_amdgcn_readfirstlane(wave) < G::LW) ring(std::true_type{});
             else ring(std::false_type{});
+            __builtin_amdgcn_s_setprio(0);
         }
     } else {
         static_assert(G::LW == G::WM * WN, "the two-stage path loads with every wave");
