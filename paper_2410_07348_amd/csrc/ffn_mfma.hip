@@ -45,7 +45,12 @@ struct GemmArgs {
     int n_ntiles;
 };
 
-__device__ inline float fast_silu(float z) { return z * __frcp_rn(1.f + __expf(-z)); }
+// silu(z) = z / (1 + e^-z) with the hardware exp2 and reciprocal (1 ulp each:
+// far inside the rounding of the bf16 result).  A correctly rounded division
+// costs ten more instructions per element, a third of the epilogue.
+__device__ inline float fast_silu(float z) {
+    return z * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * z));
+}
 
 typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
