@@ -71,6 +71,24 @@ def test_bf16_layers_all_tokens(kw, variant):
     say("errs", check_layer(s, inp, res))
 
 
+@pytest.mark.parametrize("act", ["bf16", "f32"])
+@pytest.mark.parametrize("kw", [
+    # the limits of the descriptor: N = 64 experts, K = 8 slots, 8 constant experts
+    dict(T=300, D=256, F=128, n_ffn=52, n_zero=2, n_copy=2, n_const=8, k=8, seed=95),
+    # the widest router the MFMA kernel takes: N + 2 n_const = 64 rows of weights
+    dict(T=300, D=256, F=128, n_ffn=38, n_zero=1, n_copy=1, n_const=8, k=8, seed=96),
+    # as many FFN experts as the descriptor allows, no other kind
+    dict(T=400, D=128, F=64, n_ffn=60, n_zero=0, n_copy=0, n_const=0, k=6, seed=97),
+])
+def test_maximum_expert_counts(kw, act):
+    s = small_shape("max", act=act, **kw)
+    inp = make_inputs(s)
+    say("max counts", kw, act)
+    for variant in ((1, 0) if act == "bf16" else (0,)):
+        res = gpu_forward(s, inp, variant=variant)
+        say("errs", check_layer(s, inp, res))
+
+
 @pytest.mark.parametrize("kw", [
     dict(T=200, D=64, F=96, seed=90),
     dict(T=50, D=8, F=8, n_ffn=2, n_const=1, seed=91),             # smallest legal D, F
