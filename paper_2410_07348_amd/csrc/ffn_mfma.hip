@@ -43,6 +43,7 @@ struct GemmArgs {
     int Nc;                  // columns of C (F or D)
     int n_ffn, topk;
     int n_ntiles;
+    int jstride;             // persistent kernel: workgroups per XCD
 };
 
 // silu(z) = z / (1 + e^-z) with the hardware exp2 and reciprocal (1 ulp each:
@@ -58,8 +59,9 @@ typedef __attribute__((address_space(3))) void *lptr_t;
 // Tile geometry.  BK K-elements per LDS stage; NS stages form a ring, NS - 1
 // tiles are in flight (or being computed) at any time.
 // LW_ of the WM*WN waves issue the tile loads (0: all of them).
-template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int LW_ = 0>
+template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int LW_ = 0, bool PERSIST_ = false>
 struct Geo {
+    static constexpr bool PERSIST = PERSIST_;          // one workgroup per CU runs tile after tile
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
     static constexpr int NT = WM * WN * kWave;         // threads
     static constexpr int LW = LW_ ? LW_ : WM * WN;     // waves that issue the tile loads
@@ -89,6 +91,12 @@ struct Geo {
 // asm statements keep every memory access on its side of the barrier; no
 // fence builtin is used because it would also wait for the younger
 // direct-to-LDS loads, which count as LDS writes.
+// Workgroup barrier for plain LDS traffic while direct-to-LDS loads of a later
+// tile are in flight: __syncthreads() would wait for those too.
+__device__ inline void lds_sync() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <int VM>
 __device__ inline void wait_and_barrier() {
     asm volatile("" ::: "memory");
@@ -102,18 +110,30 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     constexpr int BM = G::BM, BN = G::BN, WN = G::WN, NT = G::NT, NL = G::NL, RB = G::RB, CPR = G::CPR;
     constexpr int TM = G::TM, TN = G::TN, MB = G::MB, NB = G::NB, CA = G::CA, CB = G::CB;
     constexpr int STAGE = G::STAGE, NS = G::NS, BK = G::BK, KS = G::KS;
+    // The output tile goes through LDS in EP passes of HB rows (one pass for
+    // GEMM1, whose tile is half as wide after SwiGLU).
     constexpr int OUT_W = SWIGLU ? BN / 2 : BN;   // output tile width (elements)
     constexpr int OUT_STRIDE = OUT_W * 2 + 16;    // bytes, padded
-    constexpr int OUT_BYTES = BM * OUT_STRIDE;
+    constexpr int EP = SWIGLU ? 1 : 2;
+    constexpr int HB = BM / EP;
+    constexpr int OUT_BYTES = HB * OUT_STRIDE;
+    static_assert(TM <= HB && HB % TM == 0, "a wave's rows belong to one epilogue pass");
     constexpr int LDS_BYTES = NS * STAGE > OUT_BYTES ? NS * STAGE : OUT_BYTES;
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    // A persistent workgroup (G::PERSIST) runs tile after tile.  The stages
+    // the epilogue's LDS patch does not touch, S0 .. NS-1, take the first K
+    // tiles of the NEXT output tile while the epilogue of this one runs, so
+    // every output tile's ring starts at stage S0.
+    constexpr int S0 = G::PERSIST ? (OUT_BYTES + STAGE - 1) / STAGE : 0;
+    constexpr int EARLY = G::PERSIST ? NS - S0 : 0;      // K tiles issued before the epilogue
+    static_assert(!G::PERSIST || (EARLY >= 1 && EARLY <= NS - 1), "stages free during the epilogue");
 
     const int tid = threadIdx.x;
     const int lane = tid % kWave;
     const int wave = tid / kWave;
     const int wm = wave / WN, wn = wave % WN;
 
-    // ---- which tile --------------------------------------------------------
+    // ---- which tiles ---------------------------------------------------------
     // Workgroups are handed to the 8 XCDs round-robin by id, and every XCD has
     // its own L2.  All tiles are put in one linear order in which 32
     // consecutive tiles form a patch of GM m-tiles x GN n-tiles of one expert
@@ -121,39 +141,41 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     // on one patch at a time out of their L2.  The patches are dealt to the
     // XCDs round-robin, so at any time the 8 XCDs hold 8 neighbouring patches
     // (same rows, next columns): what one XCD fetched from HBM the others
-    // find in the memory-side cache.  Workgroup w is tile w / 8 of XCD w % 8.
-    // The order is computed here from the group offsets.
+    // find in the memory-side cache.  Tile j of XCD x is run by workgroup
+    // x + 8*(j % jstride), jstride = workgroups per XCD (persistent kernel) or
+    // by workgroup x + 8*j (one tile per workgroup).  The order is computed
+    // here from the group offsets.
     constexpr int GM = 8, GN = 4, NXCD = 8;
-    int e = 0, row0 = 0, row_end = 0, nt = 0;
-    {
-        const int Nt = a.n_ntiles;
-        // Lane q holds group q: one vector load of the offsets, a wave-wide
-        // prefix sum of the tile counts, a ballot to find the group of tile L
-        // (a scalar loop over the groups costs a dependent memory round trip
-        // per group: measured 3.9 us per workgroup with 16 groups).
-        const int q = lane < a.n_ffn ? lane : a.n_ffn;
-        const int o_lo = a.offsets[q];
-        const int o_hi = a.offsets[q < a.n_ffn ? q + 1 : q];
-        const int mt_q = (o_hi - o_lo + BM - 1) / BM;          // 0 for lanes past the last group
-        int incl = mt_q * Nt;                                   // inclusive prefix sum over lanes
+    const int Nt = a.n_ntiles;
+    // Lane q holds group q: one vector load of the offsets, a wave-wide prefix
+    // sum of the tile counts, a ballot to find the group of a tile (a scalar
+    // loop over the groups costs a dependent memory round trip per group).
+    const int gq = lane < a.n_ffn ? lane : a.n_ffn;
+    const int o_lo = a.offsets[gq];
+    const int o_hi = a.offsets[gq < a.n_ffn ? gq + 1 : gq];
+    const int mt_q = (o_hi - o_lo + BM - 1) / BM;              // 0 for lanes past the last group
+    int incl = mt_q * Nt;                                       // inclusive prefix sum over lanes
 #pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int up = __shfl_up(incl, d, kWave);
-            if (lane >= d) incl += up;
-        }
-        const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int up = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += up;
+    }
+    const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+
+    int e = 0, row0 = 0, row_end = 0, nt = 0;                  // the tile being computed
+    // tile j of this XCD -> (expert, first row, end of the group, n-tile); false past the end
+    auto locate = [&](int j, int &t_e, int &t_row0, int &t_row_end, int &t_nt) -> bool {
         // XCD x takes patch-sized chunks x, x+8, x+16, ... of the order
-        const int j = blockIdx.x / NXCD;
         int L = ((j / (GM * GN)) * NXCD + blockIdx.x % NXCD) * (GM * GN) + j % (GM * GN);
-        if (L >= total) return;
+        if (L >= total) return false;
         const unsigned long long past = __ballot(incl > L);     // lanes whose groups end after tile L
-        e = __builtin_ctzll(past);                              // L < total, so some lane has incl > L
-        // (e is the same in every lane: these are scalar reads of lane e)
-        L -= __builtin_amdgcn_readlane(incl - mt_q * Nt, e);
-        const int b = __builtin_amdgcn_readlane(o_lo, e);
-        row_end = __builtin_amdgcn_readlane(o_hi, e);
-        const int mt_e = __builtin_amdgcn_readlane(mt_q, e);
-        // inside expert e: m-groups of GM m-tiles, n-groups of GN n-tiles, m fastest
+        t_e = __builtin_ctzll(past);                            // L < total, so some lane has incl > L
+        // (t_e is the same in every lane: these are scalar reads of lane t_e)
+        L -= __builtin_amdgcn_readlane(incl - mt_q * Nt, t_e);
+        const int b = __builtin_amdgcn_readlane(o_lo, t_e);
+        t_row_end = __builtin_amdgcn_readlane(o_hi, t_e);
+        const int mt_e = __builtin_amdgcn_readlane(mt_q, t_e);
+        // inside the expert: m-groups of GM m-tiles, n-groups of GN n-tiles, m fastest
         const int n_g = (mt_e + GM - 1) / GM;
         int g = L / (GM * Nt);
         g = g < n_g - 1 ? g : n_g - 1;
@@ -164,45 +186,56 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         ng = ng < NG - 1 ? ng : NG - 1;
         L -= ng * gm * GN;
         const int mt = g * GM + L % gm;
-        nt = ng * GN + L / gm;
-        row0 = b + mt * BM;
-    }
-    const int n0 = nt * BN;
+        t_nt = ng * GN + L / gm;
+        t_row0 = b + mt * BM;
+        return true;
+    };
 
     // ---- global -> LDS, written by the load itself ----------------------------
-    // Chunk c = tid + i*NL of a tile (tid < NL: the loading waves): row c/CPR, 16-byte slot c%CPR.  One
-    // wave-wide load fills 1 KB of consecutive tile rows: lane l lands at
-    // base + 16*l.  Slot s of row r holds global chunk s ^ swz(r) of that row,
-    // so each lane fetches the global chunk that belongs in its slot.
+    // Chunk c = tid + i*NL of a tile (tid < NL: the loading waves): row c/CPR,
+    // 16-byte slot c%CPR.  One wave-wide load fills 1 KB of consecutive tile
+    // rows: lane l lands at base + 16*l.  Slot s of row r holds global chunk
+    // s ^ swz(r) of that row, so each lane fetches the global chunk that
+    // belongs in its slot.
     const int slot = tid % CPR;
     const int r_thr = tid / CPR;                 // tile row of this thread's first chunk
     const int kc = slot ^ G::swz(r_thr);         // global chunk within the K tile
     const bf16_t *pa[CA];
     const bf16_t *pb[CB];
+    size_t b_kstep = 0;                          // elements of B from one K tile to the next
+    static_assert(BN == kPanel, "one tile of B rows is one panel of the packed weights");
+    // rows of A (of x through src_of for GEMM1, of h for GEMM2) this thread loads for a tile
+    auto gather_rows = [&](int t_row0, int t_row_end, int *src) {
 #pragma unroll
-    for (int i = 0; i < CA; ++i) {
-        int r = row0 + r_thr + i * (NL / CPR);
-        r = r < row_end ? r : row_end - 1;
-        const int src = SWIGLU ? a.src_of[r] / a.topk : r;
-        // chunk kc of the tile: slab kc/4 of the tile's K range, 16-byte piece kc%4 of the slab row
-        pa[i] = SWIGLU ? a.A + (size_t)src * a.ld + kc * 8
-                       : a.A + (size_t)(kc / 4) * a.h_rows * kSlab + (size_t)src * kSlab + (kc % 4) * 8;
-    }
-    const bf16_t *Be = a.B + (size_t)e * a.Nb * a.K;
+        for (int i = 0; i < CA; ++i) {
+            int r = t_row0 + r_thr + i * (NL / CPR);
+            r = r < t_row_end ? r : t_row_end - 1;
+            src[i] = SWIGLU ? a.src_of[r] / a.topk : r;
+        }
+    };
+    auto set_pointers = [&](int t_e, int t_nt, const int *src) {
 #pragma unroll
-    for (int i = 0; i < CB; ++i) {
-        int n = n0 + r_thr + i * (NL / CPR);
-        n = n < a.Nb ? n : a.Nb - 1;
-        pb[i] = Be + panel_row(n, kc / 4, a.Nb, a.K) + (kc % 4) * 8;
-    }
+        for (int i = 0; i < CA; ++i) {
+            // chunk kc of the tile: slab kc/4 of the tile's K range, 16-byte piece kc%4 of the slab row
+            pa[i] = SWIGLU ? a.A + (size_t)src[i] * a.ld + kc * 8
+                           : a.A + (size_t)(kc / 4) * a.h_rows * kSlab + (size_t)src[i] * kSlab + (kc % 4) * 8;
+        }
+        const bf16_t *Be = a.B + (size_t)t_e * a.Nb * a.K;
+        const int n0 = t_nt * BN;
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            int n = n0 + r_thr + i * (NL / CPR);
+            n = n < a.Nb ? n : a.Nb - 1;
+            pb[i] = Be + panel_row(n, kc / 4, a.Nb, a.K) + (kc % 4) * 8;
+        }
+        const int b_rows = a.Nb - n0 < BN ? a.Nb - n0 : BN;     // rows of this tile's panel
+        b_kstep = (size_t)(BK / kSlab) * b_rows * kSlab;
+    };
     const int wave_off = __builtin_amdgcn_readfirstlane(wave) * 1024;   // this wave's 1 KB of each load group
 
     const int KT = a.K / BK;
-    // elements from one K tile to the next
+    // elements of A from one K tile to the next
     const size_t a_kstep = SWIGLU ? (size_t)BK : (size_t)(BK / kSlab) * a.h_rows * kSlab;
-    static_assert(BN == kPanel, "one tile of B rows is one panel of the packed weights");
-    const int b_rows = a.Nb - n0 < BN ? a.Nb - n0 : BN;            // rows of this tile's panel
-    const size_t b_kstep = (size_t)(BK / kSlab) * b_rows * kSlab;
     // Load q of the LPT = CA + CB wave-wide loads that make up a tile.
     auto issue_one = [&](int q, int kt, char *__restrict__ stage) {
         char *sa = stage + wave_off;
@@ -218,6 +251,13 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
 #pragma unroll
         for (int q = 0; q < CA + CB; ++q) issue_one(q, kt, stage);
     };
+    // K tiles [first, last) of the current pointers into their ring stages
+    // (tile kt: stage (S0 + kt) % NS of the ring at `ring`).  KT >= NS - 1.
+    auto issue_range = [&](int first, int last, char *__restrict__ ring) {
+#pragma unroll
+        for (int p = 0; p < NS - 1; ++p)
+            if (p >= first && p < last) issue_tile(p, ring + ((S0 + p) % NS) * STAGE);
+    };
 
     // ---- MFMA operand addressing --------------------------------------------
     // lane l reads row (l % 32) of a 32-row block, K half (l / 32) of each 16-wide step
@@ -230,12 +270,6 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     const int b_base = BM * RB + (wn * TN) * RB;
 
     f32x16 acc[NB][MB];
-#pragma unroll
-    for (int j = 0; j < NB; ++j)
-#pragma unroll
-        for (int i = 0; i < MB; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.f;
 
     auto read_frags = [&](const char *st, int ks, bf16x8 *fa, bf16x8 *fb) {
 #pragma unroll
@@ -289,187 +323,249 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     };
 
     constexpr int LPT = G::LPT;
-    // prologue: tiles 0 .. NS-2 in flight
-    auto prologue = [&]() {
-#pragma unroll
-        for (int p = 0; p < NS - 1; ++p)
-            if (p < KT) issue_tile(p, lds + p * STAGE);
-    };
 
-    if constexpr (NS >= 3) {
-        // Ring of NS stages, tile kt in stage kt % NS.  The workgroup barrier
-        // sits before the LAST MFMA step of a tile, not after it: once every
-        // wave has issued (and received) all operand reads of tile kt, the
-        // stage of tile kt-1 can be refilled and the first operands of tile
-        // kt+1 can be read, all while the matrix cores still work on the last
-        // step of tile kt.  Operands are double buffered in registers.  The
-        // loop body is branch-free (the last NS-1 tiles are peeled off), which
-        // keeps the compiler's wait-count tracking exact.  Needs KT >= NS-1.
-        static_assert(KS % 2 == 0, "operand double buffering assumes an even number of K steps");
-        // LOADER: this wave issues tile loads.  With G::LW < WM*WN only the
-        // first LW waves do; the others run the same loop without them (two
-        // copies of the loop, chosen once per wave, each branch-free inside).
-        auto ring = [&](auto loader_c) {
+    // ---- the K loop of one output tile ---------------------------------------
+    // LOADER: this wave issues tile loads.  With G::LW < WM*WN only the first
+    // LW waves do; the others run the same code without them (two copies of
+    // everything below, chosen once per wave, each free of branches around
+    // the loads).  Expects K tiles 0 .. NS-2 of the tile to be in flight.
+    auto main_loop = [&](auto loader_c) {
         constexpr bool LOADER = decltype(loader_c)::value;
-        if constexpr (LOADER) prologue();
-        // the loading waves win instruction arbitration over the others (+1 %, measured)
-        if constexpr (G::LW != G::WM * WN) __builtin_amdgcn_s_setprio(LOADER ? 2 : 0);
-        bf16x8 fa[2][MB], fb[2][NB];
-        // One tile.  cur / nxt / wr are three different stages (restrict): the
-        // loads that refill wr never make the operand reads wait.  VM = loads of
-        // younger tiles that may still be in flight when tile kt+1 is needed.
-        auto k_tile = [&](const char *__restrict__ cur, const char *__restrict__ nxt,
-                          char *__restrict__ wr, int kt_issue, auto vm_c, auto issue_c, auto last_c) {
-            constexpr int VM = decltype(vm_c)::value;
-            constexpr bool ISSUE = decltype(issue_c)::value, LAST = decltype(last_c)::value;
-            typedef std::integral_constant<int, ISSUE && LOADER ? G::LPS : 0> n_load_t;
+        if constexpr (NS >= 3) {
+            // Ring of NS stages, tile kt in stage (S0 + kt) % NS.  The workgroup
+            // barrier sits before the LAST MFMA step of a tile, not after it:
+            // once every wave has issued (and received) all operand reads of
+            // tile kt, the stage of tile kt-1 can be refilled and the first
+            // operands of tile kt+1 can be read, all while the matrix cores
+            // still work on the last step of tile kt.  Operands are double
+            // buffered in registers.  The loop body is branch-free (the last
+            // NS-1 tiles are peeled off), which keeps the compiler's wait-count
+            // tracking exact.  Needs KT >= NS-1.
+            static_assert(KS % 2 == 0, "operand double buffering assumes an even number of K steps");
+            bf16x8 fa[2][MB], fb[2][NB];
+            // One tile.  cur / nxt / wr are three different stages (restrict):
+            // the loads that refill wr never make the operand reads wait.  VM =
+            // loads of younger tiles that may still be in flight when tile kt+1
+            // is needed.
+            auto k_tile = [&](const char *__restrict__ cur, const char *__restrict__ nxt,
+                              char *__restrict__ wr, int kt_issue, auto vm_c, auto issue_c, auto last_c) {
+                constexpr int VM = decltype(vm_c)::value;
+                constexpr bool ISSUE = decltype(issue_c)::value, LAST = decltype(last_c)::value;
+                typedef std::integral_constant<int, ISSUE && LOADER ? G::LPS : 0> n_load_t;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                if (ks + 1 < KS) {
-                    // operands of this step: read during the previous step
-                    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
-                    __builtin_amdgcn_sched_barrier(0);
-                    mfma_step_mem(fa[ks & 1], fb[ks & 1], ks, true, cur, ks + 1, fa[(ks + 1) & 1],
-                                  fb[(ks + 1) & 1], n_load_t{}, kt_issue, wr);
-                } else {
-                    if constexpr (!LAST) wait_and_barrier<VM>();   // tile kt+1 landed; my reads of tile kt complete
-                    else __builtin_amdgcn_s_waitcnt(0xC07F);
-                    __builtin_amdgcn_sched_barrier(0);
-                    mfma_step_mem(fa[ks & 1], fb[ks & 1], ks, !LAST, nxt, 0, fa[0], fb[0], n_load_t{}, kt_issue, wr);
+                for (int ks = 0; ks < KS; ++ks) {
+                    if (ks + 1 < KS) {
+                        // operands of this step: read during the previous step
+                        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
+                        __builtin_amdgcn_sched_barrier(0);
+                        mfma_step_mem(fa[ks & 1], fb[ks & 1], ks, true, cur, ks + 1, fa[(ks + 1) & 1],
+                                      fb[(ks + 1) & 1], n_load_t{}, kt_issue, wr);
+                    } else {
+                        if constexpr (!LAST) wait_and_barrier<VM>();   // tile kt+1 landed; my reads of tile kt complete
+                        else __builtin_amdgcn_s_waitcnt(0xC07F);
+                        __builtin_amdgcn_sched_barrier(0);
+                        mfma_step_mem(fa[ks & 1], fb[ks & 1], ks, !LAST, nxt, 0, fa[0], fb[0], n_load_t{}, kt_issue, wr);
+                    }
                 }
-            }
-        };
-        int s_cur = 0, s_nxt = 1, s_wr = NS - 1;
-        auto rotate = [&]() {
-            s_wr = s_cur;
-            s_cur = s_nxt;
-            s_nxt = s_nxt + 1 == NS ? 0 : s_nxt + 1;
-        };
-        typedef std::true_type yes_t;
-        typedef std::false_type no_t;
-        wait_and_barrier<(NS - 2) * LPT>();     // tile 0 landed
-        read_frags(lds, 0, fa[0], fb[0]);
-        for (int kt = 0; kt < KT - (NS - 1); ++kt) {
-            k_tile(lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, kt + NS - 1,
-                   std::integral_constant<int, (NS - 3) * LPT + (KS - 1) * G::LPS>{}, yes_t{}, no_t{});
-            rotate();
-        }
-        // the last NS-1 tiles: nothing left to issue, fewer loads in flight
-        auto tail = [&](auto t_c) {
-            constexpr int t = decltype(t_c)::value;
-            if constexpr (t < NS - 1) {
-                constexpr int younger = NS - 3 - t > 0 ? NS - 3 - t : 0;
-                k_tile(lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, 0,
-                       std::integral_constant<int, younger * LPT>{}, no_t{},
-                       std::integral_constant<bool, t == NS - 2>{});
+            };
+            int s_cur = S0, s_nxt = (S0 + 1) % NS, s_wr = (S0 + NS - 1) % NS;
+            auto rotate = [&]() {
+                s_wr = s_cur;
+                s_cur = s_nxt;
+                s_nxt = s_nxt + 1 == NS ? 0 : s_nxt + 1;
+            };
+            typedef std::true_type yes_t;
+            typedef std::false_type no_t;
+            wait_and_barrier<(NS - 2) * LPT>();     // tile 0 landed
+            read_frags(lds + S0 * STAGE, 0, fa[0], fb[0]);
+            for (int kt = 0; kt < KT - (NS - 1); ++kt) {
+                k_tile(lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, kt + NS - 1,
+                       std::integral_constant<int, (NS - 3) * LPT + (KS - 1) * G::LPS>{}, yes_t{}, no_t{});
                 rotate();
             }
-        };
-        tail(std::integral_constant<int, 0>{});
-        tail(std::integral_constant<int, 1>{});
-        tail(std::integral_constant<int, 2>{});
-        tail(std::integral_constant<int, 3>{});
-        static_assert(NS <= 5, "tail unrolling covers NS - 1 <= 4 tiles");
-        };   // ring
-        if constexpr (G::LW == G::WM * WN) {
-            ring(std::true_type{});
+            // the last NS-1 tiles: nothing left to issue, fewer loads in flight
+            auto tail = [&](auto t_c) {
+                constexpr int t = decltype(t_c)::value;
+                if constexpr (t < NS - 1) {
+                    constexpr int younger = NS - 3 - t > 0 ? NS - 3 - t : 0;
+                    k_tile(lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, 0,
+                           std::integral_constant<int, younger * LPT>{}, no_t{},
+                           std::integral_constant<bool, t == NS - 2>{});
+                    rotate();
+                }
+            };
+            tail(std::integral_constant<int, 0>{});
+            tail(std::integral_constant<int, 1>{});
+            tail(std::integral_constant<int, 2>{});
+            tail(std::integral_constant<int, 3>{});
+            static_assert(NS <= 5, "tail unrolling covers NS - 1 <= 4 tiles");
         } else {
-            if (__builtin_amdgcn_readfirstlane(wave) < G::LW) ring(std::true_type{});
-            else ring(std::false_type{});
-            __builtin_amdgcn_s_setprio(0);
-        }
-    } else {
-        static_assert(G::LW == G::WM * WN, "the two-stage path loads with every wave");
-        prologue();
-        // Two stages: refill the stage that was computed last with the next
-        // tile, then run the MFMAs of this one.  `rd` and `wr` never overlap
-        // (restrict), so the operand reads are not made to wait on those loads.
-        auto k_tile = [&](const char *__restrict__ rd, char *__restrict__ wr, int kt_issue, bool issue) {
-            if (issue) issue_tile(kt_issue, wr);
+            static_assert(G::LW == G::WM * WN && !G::PERSIST, "the two-stage path loads with every wave");
+            // Two stages: refill the stage that was computed last with the next
+            // tile, then run the MFMAs of this one.  `rd` and `wr` never overlap
+            // (restrict), so the operand reads are not made to wait on those loads.
+            auto k_tile = [&](const char *__restrict__ rd, char *__restrict__ wr, int kt_issue, bool issue) {
+                if (issue) issue_tile(kt_issue, wr);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                bf16x8 fa[MB], fb[NB];
-                read_frags(rd, ks, fa, fb);
-                mfma_step(fa, fb);
+                for (int ks = 0; ks < KS; ++ks) {
+                    bf16x8 fa[MB], fb[NB];
+                    read_frags(rd, ks, fa, fb);
+                    mfma_step(fa, fb);
+                }
+            };
+            int st_rd = 0, st_wr = NS - 1;      // ring positions: tile kt lives in stage kt % NS
+            for (int kt = 0; kt < KT; ++kt) {
+                // Tile kt has landed when the loads of the younger tiles are the
+                // only ones outstanding.  The wait, the barrier and the compiler
+                // fence are one asm block so that nothing else makes this wave wait
+                // for the younger loads (a fence builtin would: those loads are LDS
+                // writes too).  lgkmcnt(0): this wave's operand reads of the
+                // previous tile are complete before any wave refills that stage.
+                if (kt + NS - 2 < KT)
+                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * LPT) : "memory");
+                else
+                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                k_tile(lds + st_rd * STAGE, lds + st_wr * STAGE, kt + NS - 1, kt + NS - 1 < KT);
+                st_rd = st_rd + 1 == NS ? 0 : st_rd + 1;
+                st_wr = st_wr + 1 == NS ? 0 : st_wr + 1;
             }
-        };
-        int st_rd = 0, st_wr = NS - 1;      // ring positions: tile kt lives in stage kt % NS
-        for (int kt = 0; kt < KT; ++kt) {
-            // Tile kt has landed when the loads of the younger tiles are the
-            // only ones outstanding.  The wait, the barrier and the compiler
-            // fence are one asm block so that nothing else makes this wave wait
-            // for the younger loads (a fence builtin would: those loads are LDS
-            // writes too).  lgkmcnt(0): this wave's operand reads of the
-            // previous tile are complete before any wave refills that stage.
-            if (kt + NS - 2 < KT)
-                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * LPT) : "memory");
-            else
-                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            k_tile(lds + st_rd * STAGE, lds + st_wr * STAGE, kt + NS - 1, kt + NS - 1 < KT);
-            st_rd = st_rd + 1 == NS ? 0 : st_rd + 1;
-            st_wr = st_wr + 1 == NS ? 0 : st_wr + 1;
         }
-    }
-    __syncthreads();                        // all waves done reading the stages
+    };
 
-    // ---- epilogue: registers -> LDS tile -> 16-byte row-contiguous stores ----
+    // ---- epilogue: registers -> LDS patch -> 16-byte stores --------------------
     // acc[j][i][v]: output row m = wm*TM + i*32 + l32,
     //               B row n = wn*TN + j*32 + 8*(v/4) + 4*lh + v%4
-    typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+    // The weight fragment is the first MFMA operand, so a lane holds four
+    // consecutive output columns of one row (8-byte LDS writes).
+    // `early` tiles of the NEXT output tile (pointers already set) are issued
+    // first; they land in stages the patch does not touch (the two restrict
+    // pointers tell the compiler so: it would otherwise wait for those loads
+    // before every LDS access below).
+    auto epilogue = [&](char *__restrict__ patch, char *__restrict__ ring, auto early_c) {
+        constexpr int N_EARLY = decltype(early_c)::value;
+        issue_range(0, N_EARLY, ring);
+        typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+        const int n0 = nt * BN;
+        const int c_col0 = SWIGLU ? n0 / 2 : n0;
+        constexpr int OCPR = OUT_W / 8;                // 16-byte chunks per output row
 #pragma unroll
-    for (int i = 0; i < MB; ++i) {
-        const int m = wm * TM + i * 32 + l32;
-        char *orow = lds + m * OUT_STRIDE;
-        if constexpr (SWIGLU) {
+        for (int ep = 0; ep < EP; ++ep) {
+            if (ep > 0) lds_sync();                    // the previous pass has left the patch
+            if ((wm * TM) / HB == ep) {
 #pragma unroll
-            for (int j = 0; j < NB; j += 2) {
-                const int c0 = (wn * TN + j * 32) / 2 + 4 * lh;   // 32 columns per block pair
+                for (int i = 0; i < MB; ++i) {
+                    const int m = wm * TM + i * 32 + l32 - ep * HB;
+                    char *orow = patch + m * OUT_STRIDE;
+                    if constexpr (SWIGLU) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 o;
+                        for (int j = 0; j < NB; j += 2) {
+                            const int c0 = (wn * TN + j * 32) / 2 + 4 * lh;   // 32 columns per block pair
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        o[q] = (bf16_t)(fast_silu(acc[j][i][4 * g + q]) * acc[j + 1][i][4 * g + q]);
-                    *reinterpret_cast<bf16x4 *>(orow + (c0 + 8 * g) * 2) = o;
+                            for (int g = 0; g < 4; ++g) {
+                                bf16x4 o;
+#pragma unroll
+                                for (int q = 0; q < 4; ++q)
+                                    o[q] = (bf16_t)(fast_silu(acc[j][i][4 * g + q]) * acc[j + 1][i][4 * g + q]);
+                                *reinterpret_cast<bf16x4 *>(orow + (c0 + 8 * g) * 2) = o;
+                            }
+                        }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < NB; ++j) {
+                            const int c0 = wn * TN + j * 32 + 4 * lh;
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) {
+                                bf16x4 o;
+#pragma unroll
+                                for (int q = 0; q < 4; ++q) o[q] = (bf16_t)acc[j][i][4 * g + q];
+                                *reinterpret_cast<bf16x4 *>(orow + (c0 + 8 * g) * 2) = o;
+                            }
+                        }
+                    }
                 }
             }
-        } else {
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const int c0 = wn * TN + j * 32 + 4 * lh;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 o;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) o[q] = (bf16_t)acc[j][i][4 * g + q];
-                    *reinterpret_cast<bf16x4 *>(orow + (c0 + 8 * g) * 2) = o;
+            lds_sync();
+            if constexpr (SWIGLU) {
+                // h is K-slab-major: the patch is OUT_W/32 slabs of HB rows x 64
+                // bytes, each consecutive in memory; consecutive threads take
+                // consecutive 16-byte pieces of a slab.
+                for (int c = tid; c < HB * OCPR; c += NT) {
+                    const int sl = c / (HB * 4), m = (c / 4) % HB, q = c % 4;
+                    const int row = row0 + ep * HB + m, col = c_col0 + sl * kSlab + q * 8;
+                    if (row < row_end && col < a.Nc)
+                        *reinterpret_cast<bf16x8 *>(a.C + (size_t)(col / kSlab) * a.h_rows * kSlab +
+                                                    (size_t)row * kSlab + q * 8) =
+                            *reinterpret_cast<const bf16x8 *>(patch + m * OUT_STRIDE + (sl * 4 + q) * 16);
+                }
+            } else {
+                for (int c = tid; c < HB * OCPR; c += NT) {
+                    const int m = c / OCPR, cc = c % OCPR;
+                    const int row = row0 + ep * HB + m, col = c_col0 + cc * 8;
+                    if (row < row_end && col < a.Nc)
+                        *reinterpret_cast<bf16x8 *>(a.C + (size_t)row * a.ld + col) =
+                            *reinterpret_cast<const bf16x8 *>(patch + m * OUT_STRIDE + cc * 16);
                 }
             }
         }
-    }
-    __syncthreads();
-    constexpr int OCPR = OUT_W / 8;                // 16-byte chunks per output row
-    const int c_col0 = SWIGLU ? n0 / 2 : n0;
-    if constexpr (SWIGLU) {
-        // h is K-slab-major: the tile is OUT_W/32 slabs of BM rows x 64 bytes,
-        // each consecutive in memory; consecutive threads take consecutive
-        // 16-byte pieces of a slab.
-        for (int c = tid; c < BM * OCPR; c += NT) {
-            const int sl = c / (BM * 4), m = (c / 4) % BM, q = c % 4;
-            const int row = row0 + m, col = c_col0 + sl * kSlab + q * 8;
-            if (row < row_end && col < a.Nc)
-                *reinterpret_cast<bf16x8 *>(a.C + (size_t)(col / kSlab) * a.h_rows * kSlab +
-                                            (size_t)row * kSlab + q * 8) =
-                    *reinterpret_cast<const bf16x8 *>(lds + m * OUT_STRIDE + (sl * 4 + q) * 16);
+    };
+
+    // ---- tile after tile -----------------------------------------------------
+    auto run = [&](auto loader_c) {
+        constexpr bool LOADER = decltype(loader_c)::value;
+        int j = blockIdx.x / NXCD;
+        if (!locate(j, e, row0, row_end, nt)) return;
+        int src[CA];
+        if constexpr (LOADER) {
+            gather_rows(row0, row_end, src);
+            set_pointers(e, nt, src);
+            issue_range(0, NS - 1, lds);
         }
+        // the loading waves win instruction arbitration over the others (+1 %, measured)
+        if constexpr (G::LW != G::WM * WN) __builtin_amdgcn_s_setprio(LOADER ? 2 : 0);
+        for (;;) {
+            // The next tile of this workgroup; the rows of x it gathers are
+            // fetched now, a whole K loop before they are needed.  When
+            // there is no next tile everything below is done once more for
+            // the tile just finished (and never used): no branch around a
+            // load, so the compiler adds no wait for one.
+            int n_e = e, n_row0 = row0, n_row_end = row_end, n_nt = nt;
+            bool more = false;
+            if constexpr (G::PERSIST) {
+                j += a.jstride;
+                more = locate(j, n_e, n_row0, n_row_end, n_nt);
+                if constexpr (LOADER) gather_rows(n_row0, n_row_end, src);
+            }
+#pragma unroll
+            for (int jj = 0; jj < NB; ++jj)
+#pragma unroll
+                for (int i = 0; i < MB; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[jj][i][v] = 0.f;
+            main_loop(loader_c);
+            __syncthreads();                    // all waves done reading the stages
+            if constexpr (!G::PERSIST) {
+                epilogue(lds, lds, std::integral_constant<int, 0>{});
+                return;
+            } else {
+                // The first K tiles of the next output tile go out before the
+                // epilogue, into the stages the epilogue does not use, the
+                // others after it.
+                if constexpr (LOADER) set_pointers(n_e, n_nt, src);
+                epilogue(lds, lds, std::integral_constant<int, LOADER ? EARLY : 0>{});
+                if (!more) break;
+                lds_sync();                     // the epilogue has left its LDS patch
+                if constexpr (LOADER) issue_range(EARLY, NS - 1, lds);
+                e = n_e; row0 = n_row0; row_end = n_row_end; nt = n_nt;
+            }
+        }
+        // loads into LDS must not outlive the workgroup
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+    if constexpr (G::LW == G::WM * WN) {
+        run(std::true_type{});
     } else {
-        for (int c = tid; c < BM * OCPR; c += NT) {
-            const int m = c / OCPR, cc = c % OCPR;
-            const int row = row0 + m, col = c_col0 + cc * 8;
-            if (row < row_end && col < a.Nc)
-                *reinterpret_cast<bf16x8 *>(a.C + (size_t)row * a.ld + col) =
-                    *reinterpret_cast<const bf16x8 *>(lds + m * OUT_STRIDE + cc * 16);
-        }
+        if (__builtin_amdgcn_readfirstlane(wave) < G::LW) run(std::true_type{});
+        else run(std::false_type{});
     }
 }
 
@@ -505,8 +601,24 @@ static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
     const long long rows = (long long)f.d.T * f.d.k;
     const long long max_mtiles = (rows + BM - 1) / BM + f.d.n_ffn;   // upper bound of sum ceil(count_e/BM)
     const long long rnd = 8 * 8 * 4;   // whole rounds of one patch (GM x GN tiles) per XCD
-    const long long blocks = (max_mtiles * a.n_ntiles + rnd - 1) / rnd * rnd;
+    long long blocks = (max_mtiles * a.n_ntiles + rnd - 1) / rnd * rnd;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    if (a.K / G::BK < G::NS - 1) return hipErrorInvalidConfiguration;   // the ring starts with NS-1 K tiles in flight
+    a.jstride = 0;
+    if (G::PERSIST) {
+        // one workgroup per CU (the LDS ring fills a CU), a multiple of 8 so that
+        // workgroup w runs on XCD w % 8 and owns tiles w/8, w/8 + jstride, ...
+        static int n_cu = 0;
+        if (n_cu == 0) {
+            int dev = 0, v = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 8)
+                v = 256;
+            n_cu = v / 8 * 8;
+        }
+        if (blocks > n_cu) blocks = n_cu;
+        a.jstride = (int)(blocks / 8);
+    }
     dim3 grid((unsigned)blocks), block(G::NT);
     if (which == 0)
         hipLaunchKernelGGL((k_grouped_gemm<G, true>), grid, block, 0, s, a);
@@ -532,7 +644,7 @@ hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
         case 2: return launch_cfg<Geo<256, 256, 2, 4, 32, 3>>(f, which, s);
         case 3: return launch_cfg<Geo<256, 256, 2, 4, 64, 2>>(f, which, s);
         case 5: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);
-        default: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4>>(f, which, s);
+        default: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true>>(f, which, s);
     }
 }
 
