@@ -114,7 +114,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     // GEMM1, whose tile is half as wide after SwiGLU).
     constexpr int OUT_W = SWIGLU ? BN / 2 : BN;   // output tile width (elements)
     constexpr int OUT_STRIDE = OUT_W * 2 + 16;    // bytes, padded
-    constexpr int EP = SWIGLU ? 1 : 2;
+    constexpr int EP = SWIGLU || BM < 256 ? 1 : 2;
     constexpr int HB = BM / EP;
     constexpr int OUT_BYTES = HB * OUT_STRIDE;
     static_assert(TM <= HB && HB % TM == 0, "a wave's rows belong to one epilogue pass");
@@ -634,16 +634,21 @@ hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
     // at least 4 K tiles; shorter reductions use two 64-deep stages.
     // MOEPP_GEMM_CFG selects other geometries, for tuning: 1 = 4 waves with
     // 128x128 wave tiles, 2 = ring of 3, 3 = two 64-deep stages, 5 = every
-    // wave loads.
+    // wave loads, 7 = 128-row tiles.
     const char *v = getenv("MOEPP_GEMM_CFG");
     int cfg = v ? atoi(v) : 0;
     const int K = which == 0 ? f.d.D : f.d.F;
+    // Few rows per expert (decoding, small batches): the GEMMs only stream
+    // the weights, so use 128-row tiles: half of the (mostly wasted)
+    // matrix work of a 256-row tile per byte of weights, bound by HBM instead.
+    if (cfg == 0 && (long long)f.d.T * f.d.k <= 128ll * f.d.n_ffn) cfg = 7;
     if (K / 32 < 4) cfg = 3;              // too few K tiles to fill a ring of stages
     switch (cfg) {
         case 1: return launch_cfg<Geo<256, 256, 2, 2, 32, 5>>(f, which, s);
         case 2: return launch_cfg<Geo<256, 256, 2, 4, 32, 3>>(f, which, s);
         case 3: return launch_cfg<Geo<256, 256, 2, 4, 64, 2>>(f, which, s);
         case 5: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);
+        case 7: return launch_cfg<Geo<128, 256, 1, 4, 32, 5, 0, true>>(f, which, s);
         default: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true>>(f, which, s);
     }
 }
