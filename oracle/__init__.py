@@ -42,7 +42,9 @@ def lib():
         _lib = ctypes.CDLL(build())
         _lib.moepp_oracle_threads.restype = ctypes.c_int
         for f in ("moepp_oracle_route", "moepp_oracle_permute",
-                  "moepp_oracle_experts", "moepp_oracle_dense"):
+                  "moepp_oracle_experts", "moepp_oracle_dense",
+                  "moepp_oracle_capacity", "moepp_oracle_permute_capacity",
+                  "moepp_oracle_balance"):
             getattr(_lib, f).restype = ctypes.c_int
     return _lib
 
@@ -119,9 +121,63 @@ def permute(sh, topk_idx):
     return {"counts": counts, "offsets": offsets, "row_of": row_of, "src_of": src_of}
 
 
+def capacity(sh, gamma, tau):
+    """Expert capacities C_i of Eq.8 (int32 [N]) for T*K assignments."""
+    cs = _cshape(sh.T, sh.D, sh.F, sh.n_ffn, sh.n_zero, sh.n_copy, sh.n_const, sh.k)
+    N = sh.n_ffn + sh.n_zero + sh.n_copy + sh.n_const
+    cap = np.empty(N, np.int32)
+    rc = lib().moepp_oracle_capacity(ctypes.byref(cs), ctypes.c_double(gamma),
+                                     ctypes.c_double(tau), _p(cap, np.int32))
+    if rc != 0:
+        raise ValueError("moepp_oracle_capacity: gamma and tau must be positive")
+    return cap
+
+
+def permute_capacity(sh, topk_idx, cap):
+    """Grouping in which expert i keeps its first cap[i] assignments."""
+    cs = _cshape(sh.T, sh.D, sh.F, sh.n_ffn, sh.n_zero, sh.n_copy, sh.n_const, sh.k)
+    N = sh.n_ffn + sh.n_zero + sh.n_copy + sh.n_const
+    idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
+    cap = np.ascontiguousarray(cap, dtype=np.int32)
+    assert idx.shape == (sh.T, sh.k) and cap.shape == (N,)
+    counts = np.empty(N, np.int32)
+    kept = np.empty(N, np.int32)
+    offsets = np.empty(sh.n_ffn + 1, np.int32)
+    row_of = np.empty(sh.T * sh.k, np.int32)
+    src_of = np.empty(sh.T * sh.k, np.int32)
+    rc = lib().moepp_oracle_permute_capacity(ctypes.byref(cs), _p(idx, np.int32),
+                                             _p(cap, np.int32), _p(counts, np.int32),
+                                             _p(kept, np.int32), _p(offsets, np.int32),
+                                             _p(row_of, np.int32), _p(src_of, np.int32))
+    if rc != 0:
+        raise ValueError("moepp_oracle_permute_capacity: bad expert index or capacity")
+    return {"counts": counts, "kept": kept, "offsets": offsets, "row_of": row_of,
+            "src_of": src_of}
+
+
+def balance(sh, probs, topk_idx, tau):
+    """f_i, P_i and the heterogeneous load-balance loss L_b of Eq.7."""
+    cs = _cshape(sh.T, sh.D, sh.F, sh.n_ffn, sh.n_zero, sh.n_copy, sh.n_const, sh.k)
+    N = sh.n_ffn + sh.n_zero + sh.n_copy + sh.n_const
+    probs = np.ascontiguousarray(probs, dtype=np.float64)
+    idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
+    assert probs.shape == (sh.T, N) and idx.shape == (sh.T, sh.k)
+    f = np.empty(N, np.float64)
+    P = np.empty(N, np.float64)
+    loss = np.empty(1, np.float64)
+    rc = lib().moepp_oracle_balance(ctypes.byref(cs), _p(probs, np.float64),
+                                    _p(idx, np.int32), ctypes.c_double(tau),
+                                    _p(f, np.float64), _p(P, np.float64),
+                                    _p(loss, np.float64))
+    if rc != 0:
+        raise ValueError("moepp_oracle_balance: needs at least one token")
+    return {"f": f, "P": P, "loss": float(loss[0])}
+
+
 def experts(sh, x, topk_idx, topk_w, w1, w3, w2, const_vecs, W_c, tok_list=None,
-            want_slots=False, want_h=False, want_alpha=False):
-    """Selected experts (Eq.2-5) and their weighted sum (Eq.1) per token."""
+            want_slots=False, want_h=False, want_alpha=False, row_of=None):
+    """Selected experts (Eq.2-5) and their weighted sum (Eq.1) per token;
+    assignments with row_of == -2 (dropped by the capacity) are left out."""
     cs = _cshape(sh.T, sh.D, sh.F, sh.n_ffn, sh.n_zero, sh.n_copy, sh.n_const, sh.k)
     x, w1, w3, w2, const_vecs, W_c = map(_f32, (x, w1, w3, w2, const_vecs, W_c))
     idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
@@ -135,6 +191,9 @@ def experts(sh, x, topk_idx, topk_w, w1, w3, w2, const_vecs, W_c, tok_list=None,
     else:
         tl = np.ascontiguousarray(tok_list, dtype=np.int32)
         n_tok = int(tl.size)
+    if row_of is not None:
+        row_of = np.ascontiguousarray(row_of, dtype=np.int32)
+        assert row_of.shape == (sh.T * sh.k,)
     out = np.empty((n_tok, sh.D), np.float64)
     slots = np.zeros((n_tok, sh.k, sh.D), np.float64) if want_slots else None
     h = np.zeros((n_tok, sh.k, sh.F), np.float64) if want_h else None
@@ -143,7 +202,8 @@ def experts(sh, x, topk_idx, topk_w, w1, w3, w2, const_vecs, W_c, tok_list=None,
                                     _p(idx, np.int32), _p(w, np.float32),
                                     _p(w1, np.float32), _p(w3, np.float32),
                                     _p(w2, np.float32), _p(const_vecs, np.float32),
-                                    _p(W_c, np.float32), ctypes.c_int32(n_tok),
+                                    _p(W_c, np.float32), _p(row_of, np.int32),
+                                    ctypes.c_int32(n_tok),
                                     _p(tl, np.int32), _p(out, np.float64),
                                     _p(slots, np.float64), _p(h, np.float64),
                                     _p(a1, np.float64))
@@ -172,13 +232,19 @@ def dense(sh, x, gate, w1, w3, w2, const_vecs, W_c):
     return out
 
 
-def layer_forward(sh, inp, forced_idx=None, tok_list=None, **want):
+def layer_forward(sh, inp, forced_idx=None, tok_list=None, cap=None, **want):
     """Whole layer: route -> permute -> experts.  `inp` is a dict with the
-    tensor names of workloads.make_inputs."""
+    tensor names of workloads.make_inputs; `cap` [N] are expert capacities
+    (None: unlimited)."""
     r = route(sh, inp["x"], inp.get("prev_gate"), inp["W_g"], inp.get("W_res"),
               inp.get("bias"), forced_idx=forced_idx, want_probs=True)
-    r.update(permute(sh, r["topk_idx"]))
+    if cap is None:
+        r.update(permute(sh, r["topk_idx"]))
+        row_of = None
+    else:
+        r.update(permute_capacity(sh, r["topk_idx"], cap))
+        row_of = r["row_of"]
     r.update(experts(sh, inp["x"], r["topk_idx"], r["topk_w"], inp["w1"], inp["w3"],
                      inp["w2"], inp["const_vecs"], inp["W_c"], tok_list=tok_list,
-                     **want))
+                     row_of=row_of, **want))
     return r

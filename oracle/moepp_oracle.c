@@ -29,11 +29,24 @@
  *  - logits are rounded once to float32 (the type they are handed to the
  *    next layer in) and softmax / Top-K read those float32 values;
  *  - the optional per-expert additive router bias is a benchmark knob that
- *    the paper does not have; it is part of G(x) when present.
+ *    the paper does not have; it is part of G(x) when present;
+ *  - expert capacity (Eq.8): the "number of tokens T" of that equation is
+ *    read as the number of (token, slot) assignments T*K (with T itself the
+ *    capacities of Eq.8 sum to gamma*T for K*T assignments, so that at
+ *    K = 2, gamma = 1.1 almost half of all assignments would be dropped);
+ *    C_i is rounded up to an integer; an expert keeps the first C_i of the
+ *    assignments it received in (token, slot) order and the others are
+ *    dropped: a dropped assignment contributes nothing to y (the token
+ *    reaches the next block through the residual connection around the
+ *    layer), the gate weights of the kept ones are not renormalised;
+ *  - f_i of Eq.7 counts the tokens that selected expert i before any drop.
  *
  * Pins: tests/test_oracle_*.py check this file against closed forms of
  * Eq.3-5, invariants of Eq.1 and Eq.6, hand-computed examples, a dense
- * "all experts then mask" evaluation of Eq.1 and a textbook top-k MoE.
+ * "all experts then mask" evaluation of Eq.1 and a textbook top-k MoE; the
+ * capacity and load-balance functions against Eq.7 / Eq.8 worked by hand,
+ * their closed forms for uniform routing and the textbook token-dropping
+ * rule they reduce to without zero-computation experts.
  */
 #include <math.h>
 #include <stdint.h>
@@ -202,6 +215,118 @@ int moepp_oracle_permute(const oracle_shape *s, const int32_t *topk_idx,
     return 0;
 }
 
+/*
+ * Expert capacity, Eq.8: C_i = gamma * tau * S / (tau N_FFN + N_ZC) for an FFN
+ * expert and gamma * S / (tau N_FFN + N_ZC) for a zero-computation expert,
+ * rounded up (a relative 1e-9 above an integer counts as that integer), with
+ * S = T*K assignments (see the readings in the header).
+ *   cap [N] int32
+ */
+int moepp_oracle_capacity(const oracle_shape *s, double gamma, double tau,
+                          int32_t *cap)
+{
+    const int N = n_experts(s);
+    const int n_zc = N - s->n_ffn;
+    const double denom = tau * (double)s->n_ffn + (double)n_zc;
+    if (!(gamma > 0.0) || !(tau > 0.0) || !(denom > 0.0))
+        return -1;
+    const double S = (double)s->T * (double)s->k;
+    for (int i = 0; i < N; ++i) {
+        const double c = i < s->n_ffn ? gamma * tau * S / denom : gamma * S / denom;
+        /* round up, but take a value that exceeds an integer only by the
+         * representation error of gamma and tau (1.1 * 200 / 10 evaluates
+         * to 22.000000000000004) as that integer */
+        cap[i] = (int32_t)ceil(c - 1e-9 * (c > 1.0 ? c : 1.0));
+    }
+    return 0;
+}
+
+/*
+ * Grouping with expert capacities: as moepp_oracle_permute, but expert i
+ * keeps only the first cap[i] of its assignments in (token, slot) order.
+ *
+ *   counts [N]        assignments per expert before any drop
+ *   kept   [N]        min(counts[i], cap[i])
+ *   offsets[n_ffn+1]  exclusive prefix sum of kept over the FFN experts
+ *   row_of [T*K]      row of a kept FFN assignment; -1 for a kept assignment
+ *                     of a zero-computation expert; -2 for a dropped one
+ *   src_of [T*K]      first R = offsets[n_ffn] entries: assignment of each row
+ */
+int moepp_oracle_permute_capacity(const oracle_shape *s, const int32_t *topk_idx,
+                                  const int32_t *cap, int32_t *counts,
+                                  int32_t *kept, int32_t *offsets,
+                                  int32_t *row_of, int32_t *src_of)
+{
+    const int N = n_experts(s), K = s->k, T = s->T;
+    for (int i = 0; i < N; ++i) {
+        counts[i] = 0;
+        if (cap[i] < 0)
+            return -1;
+    }
+    for (int q = 0; q < T * K; ++q) {
+        int e = topk_idx[q];
+        if (e < 0 || e >= N)
+            return -1;
+        counts[e] += 1;
+        src_of[q] = -1;
+    }
+    for (int i = 0; i < N; ++i)
+        kept[i] = counts[i] < cap[i] ? counts[i] : cap[i];
+    offsets[0] = 0;
+    for (int e = 0; e < s->n_ffn; ++e)
+        offsets[e + 1] = offsets[e] + kept[e];
+    /* walk the assignments in (token, slot) order, one running rank per expert */
+    int32_t *rank = (int32_t *)calloc(N > 0 ? N : 1, sizeof(int32_t));
+    for (int q = 0; q < T * K; ++q) {
+        const int e = topk_idx[q];
+        const int r = rank[e]++;
+        if (r >= cap[e]) {
+            row_of[q] = -2;
+        } else if (e < s->n_ffn) {
+            row_of[q] = offsets[e] + r;
+            src_of[offsets[e] + r] = q;
+        } else {
+            row_of[q] = -1;
+        }
+    }
+    free(rank);
+    return 0;
+}
+
+/*
+ * Heterogeneous load-balance statistics, Eq.7:
+ *   f_i = (1/T) #{tokens that selected expert i},  P_i = (1/T) sum_t Softmax(G(x_t))_i,
+ *   L_b = sum_i eta_i f_i P_i,  eta_i = 1 (FFN expert) or tau (zero-computation expert).
+ *   probs [T,N] float64 (Softmax(G(x)) from moepp_oracle_route), topk_idx [T,K]
+ *   f, P [N] float64; loss [1] float64
+ */
+int moepp_oracle_balance(const oracle_shape *s, const double *probs,
+                         const int32_t *topk_idx, double tau, double *f,
+                         double *P, double *loss)
+{
+    const int N = n_experts(s), K = s->k, T = s->T;
+    if (T <= 0)
+        return -1;
+    for (int i = 0; i < N; ++i) {
+        f[i] = 0.0;
+        P[i] = 0.0;
+    }
+    for (int t = 0; t < T; ++t) {
+        for (int sl = 0; sl < K; ++sl)
+            f[topk_idx[(size_t)t * K + sl]] += 1.0;
+        for (int i = 0; i < N; ++i)
+            P[i] += probs[(size_t)t * N + i];
+    }
+    double L = 0.0;
+    for (int i = 0; i < N; ++i) {
+        f[i] /= (double)T;
+        P[i] /= (double)T;
+        L += (i < s->n_ffn ? 1.0 : tau) * f[i] * P[i];
+    }
+    *loss = L;
+    return 0;
+}
+
 /* output of expert i for one token: e[D] (fp64).  xf is the token in fp64. */
 static void expert_output(const oracle_shape *s, int i, const double *xf,
                           const float *w1, const float *w3, const float *w2,
@@ -263,6 +388,8 @@ static void expert_output(const oracle_shape *s, int i, const double *xf,
  *   w1, w3 [n_ffn,F,D], w2 [n_ffn,D,F], const_vecs [n_const,D],
  *   W_c [n_const,2,D]    float32
  *   topk_idx/topk_w [T,K] as written by moepp_oracle_route
+ *   row_of [T*K] int32 or NULL: assignments with row_of == -2 were dropped by
+ *                the expert capacity and contribute nothing
  * outputs (row u belongs to token tok_list[u])
  *   out     [n_tok,D]        float64  y = sum_s g_s E_s(x)
  *   slot_out[n_tok,K,D]      float64 or NULL  E_s(x) of each selected expert
@@ -275,6 +402,7 @@ int moepp_oracle_experts(const oracle_shape *s, const float *x,
                          const int32_t *topk_idx, const float *topk_w,
                          const float *w1, const float *w3, const float *w2,
                          const float *const_vecs, const float *W_c,
+                         const int32_t *row_of,
                          int32_t n_tok, const int32_t *tok_list, double *out,
                          double *slot_out, double *h_out, double *alpha1)
 {
@@ -300,6 +428,8 @@ int moepp_oracle_experts(const oracle_shape *s, const float *x,
         for (int sl = 0; sl < K; ++sl) {
             const int i = topk_idx[(size_t)t * K + sl];
             const double g = (double)topk_w[(size_t)t * K + sl];
+            if (row_of && row_of[(size_t)t * K + sl] == -2)
+                continue;                       /* dropped: over capacity */
             expert_output(s, i, xf, w1, w3, w2, const_vecs, W_c, e, h, NULL);
             for (int d = 0; d < D; ++d)
                 y[d] += g * e[d];
