@@ -37,8 +37,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def run_gpu(shape, inp, steps, warmup):
-    """Timed steps of moepp_layer_forward on cuda:0.  Returns a dict."""
+def run_gpu(shape, inp, steps, warmup, capacity=None):
+    """Timed steps of moepp_layer_forward on cuda:0.  Returns a dict.
+    capacity = (gamma, tau): expert capacities of Eq.8 and the statistics of Eq.7 on."""
     import torch
     from helpers import make_layer, to_device
     dev = to_device(shape, inp)
@@ -47,6 +48,11 @@ def run_gpu(shape, inp, steps, warmup):
     for k in ("w1", "w3", "w2"):          # only the packed copy is needed from here on
         dev[k] = None
     L.set_router_bias(dev.get("bias"))
+    cap = None
+    if capacity:
+        cap = L.capacity(shape.T, capacity[0], capacity[1])
+        L.set_capacity(cap)
+        L.set_balance(capacity[1])
     cv = dev["const_vecs"] if shape.n_const else None
     wc = dev["W_c"] if shape.n_const else None
     out = torch.empty((shape.T, shape.D), dtype=L.act_dtype, device=L.device)
@@ -72,7 +78,9 @@ def run_gpu(shape, inp, steps, warmup):
     counts = r["counts"].cpu().numpy().copy()
     R = int(r["offsets"][-1].item()) if shape.n_ffn else 0
     res = {"ms_per_step": wall / steps * 1e3, "kernel_ms": kern, "R": R,
-           "counts": counts.tolist(),
+           "counts": counts.tolist(), "cap": cap,
+           "kept": L.get_kept().cpu().numpy().tolist(),
+           "loss": float(L.get_balance()["loss"].item()) if capacity else None,
            "topk_idx": r["topk_idx"].cpu().numpy().copy(),
            "out": out, "layer": L, "dev": dev}
     return res
@@ -206,7 +214,8 @@ def main():
 
     # ---- vanilla MoE: same T/D/F/k, zero-computation experts disabled --------
     if not args.no_vanilla and shape.n_zc > 0 and shape.name == "large":
-        del g["layer"], g["dev"], g["out"]
+        for k_ in ("layer", "dev", "out"):
+            g.pop(k_, None)
         torch.cuda.empty_cache()
         van = {}
         for vname in ("large_vanilla16", "large_vanilla20"):
@@ -231,6 +240,24 @@ def main():
         result["tab1_fraction_tau1"] = ffn_work_fraction(1.0, shape.n_ffn, shape.n_zc)
         result["paper_context"] = "paper Tab.3: 1.1-2.1x expert forward throughput vs vanilla MoE " \
                                   "(A100 cluster, other shapes); context only"
+
+    # ---- the same layer with the paper's expert capacities (Sec. 3.3) ----------
+    if not args.no_vanilla and shape.n_ffn > 0:
+        for k in ("layer", "dev", "out"):
+            g.pop(k, None)
+        torch.cuda.empty_cache()
+        gamma, tau = 1.1, 0.75               # the paper's capacity factor and default tau
+        gc = run_gpu(shape, inp, args.steps, args.warmup, capacity=(gamma, tau))
+        slots = shape.T * shape.k
+        result["with_capacity"] = {
+            "gamma": gamma, "tau": tau, "ms_per_step": gc["ms_per_step"], "R": gc["R"],
+            "tokens_per_s": shape.T / (gc["ms_per_step"] * 1e-3),
+            "dropped_fraction": 1.0 - sum(gc["kept"]) / slots,
+            "capacity_ffn": gc["cap"][0], "capacity_zc": gc["cap"][-1] if shape.n_zc else None,
+            "load_balance_loss": gc["loss"], "kernel_ms": gc["kernel_ms"]}
+        log("with capacity", result["with_capacity"])
+        del gc
+        torch.cuda.empty_cache()
 
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a sample")

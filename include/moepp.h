@@ -181,11 +181,12 @@ moepp_status moepp_combine(moepp_ctx *ctx, void *stream, int32_t T,
  * output pointer may be NULL.  With T and k of that call:
  *   topk_idx [T,k] int32   selected experts, descending logit
  *   topk_w   [T,k] float32 their gate weights g_i
- *   counts   [N]   int32   slots per expert (sum = T*k)
- *   offsets  [n_ffn+1] int32  exclusive scan of counts over FFN experts;
+ *   counts   [N]   int32   slots per expert (sum = T*k), before any drop
+ *   offsets  [n_ffn+1] int32  exclusive scan of the kept slots (= counts
+ *                             without capacities) over the FFN experts;
  *                             offsets[n_ffn] = R = rows that reach an FFN
  *   row_of   [T*k] int32   row in [0,R) of slot t*k+s, -1 for zero-computation
- *                          experts
+ *                          experts, -2 for a slot dropped by an expert capacity
  *   src_of   [T*k] int32   first R entries: the slot t*k+s of each row; rows of
  *                          one expert are in ascending slot order
  */
@@ -222,10 +223,53 @@ enum {
     MOEPP_K_GEMM1 = 4,   /* grouped GEMM W1/W3 + SwiGLU                       */
     MOEPP_K_GEMM2 = 5,   /* grouped GEMM W2                                   */
     MOEPP_K_COMBINE = 6, /* weighted combine + zero-computation experts       */
-    MOEPP_NUM_KERNELS = 7
+    MOEPP_K_BALANCE = 7, /* load-balance statistics (only when switched on)    */
+    MOEPP_NUM_KERNELS = 8
 };
 moepp_status moepp_set_timing(moepp_ctx *ctx, int32_t enable);
 moepp_status moepp_get_timing(moepp_ctx *ctx, float *ms);
+
+/*
+ * Expert capacity (Sec. 3.3, Eq.8).  moepp_capacity is host arithmetic: it
+ * writes into cap_host[N] (host array)
+ *   C_i = ceil(gamma * tau * S / (tau N_FFN + N_ZC))   for an FFN expert,
+ *   C_i = ceil(gamma * S / (tau N_FFN + N_ZC))         for a zero-computation expert,
+ * with S = T * k, the number of (token, slot) assignments of a call (Eq.8's
+ * "number of tokens" is read as the assignments: with T itself the capacities
+ * would add up to gamma*T places for k*T assignments).  A value that exceeds
+ * an integer by less than 1e-9 relative counts as that integer.
+ * EINVAL: null pointer, T or k outside the descriptor, gamma or tau not positive.
+ *
+ * moepp_set_capacity copies cap_host[N] into the context (NULL switches the
+ * capacities off, the default).  From then on moepp_permute and
+ * moepp_layer_forward let expert i keep only the first cap_host[i] of its
+ * assignments in (token, slot) order; the others are dropped: they get
+ * row_of = -2, reach no GEMM and add nothing to `out` (the token continues
+ * through the residual connection around the layer); gate weights are not
+ * renormalised.  counts (moepp_get_routing) stay the numbers before the drop,
+ * moepp_get_kept gives min(counts, cap) [N] int32 on the device, offsets
+ * are the prefix sums of the kept FFN rows.  EINVAL: a negative capacity.
+ */
+moepp_status moepp_capacity(const moepp_desc *desc, int32_t T, int32_t k, double gamma,
+                            double tau, int32_t *cap_host);
+moepp_status moepp_set_capacity(moepp_ctx *ctx, const int32_t *cap_host);
+moepp_status moepp_get_kept(moepp_ctx *ctx, const int32_t **kept);
+
+/*
+ * Heterogeneous load-balance statistics (Sec. 3.3, Eq.7), by-products of the
+ * routing: f_i = fraction of the tokens that selected expert i (before any
+ * drop), P_i = mean of Softmax(G(x))_i over the tokens, L_b = sum_i eta_i
+ * f_i P_i with eta_i = 1 for FFN experts and tau for zero-computation
+ * experts.  moepp_set_balance(tau > 0) switches them on (tau <= 0: off, the
+ * default); moepp_permute / moepp_layer_forward then compute them after the
+ * permutation from the logits of the routed call the permutation belongs to
+ * (out_gate of that call must still be intact; moepp_permute without a
+ * preceding moepp_route of the same T is EINVAL while they are on).
+ * moepp_get_balance returns device pointers: f [N], P [N], loss [1] float32.
+ */
+moepp_status moepp_set_balance(moepp_ctx *ctx, double tau);
+moepp_status moepp_get_balance(moepp_ctx *ctx, const float **f, const float **P,
+                               const float **loss);
 
 /*
  * Kernel-variant selection, for tests and tuning: 0 = automatic (default),

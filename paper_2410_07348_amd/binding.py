@@ -9,14 +9,16 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 F32, BF16 = 0, 1
 OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP = 0, -1, -2, -3, -4
 KERNEL_NAMES = ("router", "perm_hist", "perm_scan", "perm_scatter", "gemm1", "gemm2",
-                "combine")
+                "combine", "balance")
 
 # every symbol include/moepp.h declares
 EXPORTS = ("moepp_workspace_bytes", "moepp_packed_bytes", "moepp_create", "moepp_destroy",
            "moepp_pack_experts", "moepp_set_router_bias", "moepp_layer_forward",
            "moepp_route", "moepp_permute", "moepp_expert_ffn", "moepp_combine",
            "moepp_get_routing", "moepp_get_intermediates", "moepp_set_timing",
-           "moepp_get_timing", "moepp_set_variant", "moepp_mfma_ceiling", "moepp_status_str")
+           "moepp_get_timing", "moepp_set_variant", "moepp_mfma_ceiling", "moepp_status_str",
+           "moepp_capacity", "moepp_set_capacity", "moepp_get_kept", "moepp_set_balance",
+           "moepp_get_balance")
 
 
 class MoeppError(RuntimeError):
@@ -80,6 +82,12 @@ def load_library(build_if_missing: bool = True):
     L.moepp_get_timing.argtypes = [vp, POINTER(c_float)]
     L.moepp_set_variant.argtypes = [vp, i32]
     L.moepp_mfma_ceiling.argtypes = [vp, vp, c_size_t, i32, POINTER(ctypes.c_double)]
+    L.moepp_capacity.argtypes = [POINTER(Desc), i32, i32, ctypes.c_double, ctypes.c_double,
+                                 POINTER(c_int32)]
+    L.moepp_set_capacity.argtypes = [vp, POINTER(c_int32)]
+    L.moepp_get_kept.argtypes = [vp, POINTER(vp)]
+    L.moepp_set_balance.argtypes = [vp, ctypes.c_double]
+    L.moepp_get_balance.argtypes = [vp] + [POINTER(vp)] * 3
     L.moepp_status_str.restype = c_char_p
     L.moepp_status_str.argtypes = [i32]
     for n in EXPORTS:
@@ -260,6 +268,37 @@ class Layer:
             "row_of": self._view(p[4].value, T * k, t.int32),
             "src_of": self._view(p[5].value, T * k, t.int32),
         }
+
+    def capacity(self, T, gamma, tau, k=None):
+        """Expert capacities C_i of Eq.8 for a call with T tokens: list of N ints."""
+        cap = (c_int32 * self.desc.N)()
+        _check(self.L.moepp_capacity(byref(self.desc), T, self.desc.k if k is None else k,
+                                     gamma, tau, cap), "moepp_capacity")
+        return [int(v) for v in cap]
+
+    def set_capacity(self, cap):
+        """Per-expert capacities for the following calls (None: unlimited)."""
+        if cap is None:
+            _check(self.L.moepp_set_capacity(self.ctx, None), "moepp_set_capacity")
+            return
+        arr = (c_int32 * self.desc.N)(*[int(v) for v in cap])
+        _check(self.L.moepp_set_capacity(self.ctx, arr), "moepp_set_capacity")
+
+    def get_kept(self):
+        p = c_void_p()
+        _check(self.L.moepp_get_kept(self.ctx, byref(p)), "moepp_get_kept")
+        return self._view(p.value, self.desc.N, self.torch.int32)
+
+    def set_balance(self, tau):
+        """Collect f_i, P_i, L_b of Eq.7 with this tau (<= 0: off)."""
+        _check(self.L.moepp_set_balance(self.ctx, float(tau)), "moepp_set_balance")
+
+    def get_balance(self):
+        p = [c_void_p() for _ in range(3)]
+        _check(self.L.moepp_get_balance(self.ctx, *[byref(q) for q in p]), "moepp_get_balance")
+        f32, N = self.torch.float32, self.desc.N
+        return {"f": self._view(p[0].value, N, f32), "P": self._view(p[1].value, N, f32),
+                "loss": self._view(p[2].value, 1, f32)}
 
     def get_intermediates(self, R=None):
         """alpha1 [T,n_const]; h [R,F]; yffn [R,D] (R rows reach an FFN)."""

@@ -7,6 +7,7 @@
 //     zero expert     : E = 0                          (nothing is read)
 //     copy expert     : E = x_t
 //     constant expert : E = a1 x_t + (1 - a1) v_j
+//     any expert, slot dropped by the expert capacity (row_of = -2): nothing
 // fp32 accumulation, one rounding to the activation type.  HBM-bound: one
 // wavefront streams one token with 16-byte accesses per lane.
 #include "common.h"
@@ -36,9 +37,12 @@ __global__ __launch_bounds__(kCombineWaves *kWave) void k_combine(CombineArgs a)
         if (s < K) {
             const int i = a.topk_idx[(size_t)t * K + s];
             const float g = a.topk_w[(size_t)t * K + s];
-            if (i < zero0) {
+            const int row = a.row_of[(size_t)t * K + s];
+            if (row == -2) {
+                // over the expert's capacity: dropped
+            } else if (i < zero0) {
                 g_row[s] = g;
-                p_row[s] = static_cast<const AT *>(a.yffn) + (size_t)a.row_of[(size_t)t * K + s] * D;
+                p_row[s] = static_cast<const AT *>(a.yffn) + (size_t)row * D;
             } else if (i < copy0) {
                 // zero expert: contributes nothing
             } else if (i < const0) {

@@ -71,7 +71,8 @@ struct Workspace {
     int32_t *topk_idx;   // [T_max*k]
     float *topk_w;       // [T_max*k]
     float *alpha1;       // [T_max*n_const]
-    int32_t *counts;     // [N]
+    int32_t *counts;     // [N] assignments per expert, before any drop
+    int32_t *kept;       // [N] min(counts, capacity)
     int32_t *offsets;    // [n_ffn+1]
     int32_t *row_of;     // [T_max*k]
     int32_t *src_of;     // [T_max*k]
@@ -80,7 +81,17 @@ struct Workspace {
     void *h;             // [T_max*k, F] act, K-slab-major
     void *yffn;          // [T_max*k, D] act
     void *wsplit;        // router_split_bytes(D, N + 2 n_const)
+    double *bal_partial; // [kBalWaves][kMaxExperts] partial sums of Softmax(G(x))
+    float *bal;          // f [N], P [N], L_b [1]  (Eq.7)
 };
+
+// Expert capacities (Eq.8), by value in the kernel arguments.  on = false: unlimited.
+struct CapArgs {
+    bool on;
+    int32_t cap[kMaxExperts];
+};
+
+constexpr int kBalWaves = 2048;   // waves of the load-balance reduction (its partial sums)
 
 struct RouterArgs {
     Dims d;
@@ -121,8 +132,11 @@ hipError_t launch_router_mfma(const RouterArgs &a, hipStream_t s);
 size_t router_split_bytes(int D, int rows);
 
 hipError_t launch_perm_hist(const Dims &d, const Workspace &w, hipStream_t s);
-hipError_t launch_perm_scan(const Dims &d, const Workspace &w, hipStream_t s);
-hipError_t launch_perm_scatter(const Dims &d, const Workspace &w, hipStream_t s);
+hipError_t launch_perm_scan(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s);
+hipError_t launch_perm_scatter(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s);
+// f_i, P_i and L_b of Eq.7 from the logits of the routed call and the counts of the permutation
+hipError_t launch_balance(const Dims &d, const Workspace &w, const float *out_gate, float tau,
+                          hipStream_t s);
 
 hipError_t launch_ffn_generic(const FfnArgs &a, bool bf16, int which, hipStream_t s);
 bool ffn_mfma_supported(const Dims &d);

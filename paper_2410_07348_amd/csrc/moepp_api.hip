@@ -4,6 +4,8 @@
 #include "../../include/moepp.h"
 #include "common.h"
 
+#include <math.h>
+
 #include <new>
 
 using namespace moepp;
@@ -16,6 +18,9 @@ struct moepp_ctx {
     size_t ws_bytes;
     const float *bias;
     int variant;          // 0 auto, 1 generic, 2 require MFMA
+    CapArgs cap;          // expert capacities (Eq.8); cap.on = false: unlimited
+    double bal_tau;       // > 0: collect the load-balance statistics (Eq.7) with this tau
+    const float *last_out_gate;   // logits of the last routed call (read by the statistics)
     int last_T, last_k;
     bool timing;
     bool have_events;
@@ -65,6 +70,7 @@ size_t layout(const moepp_desc *d, char *base, Workspace *ws) {
     w.topk_w = (float *)take(slots * 4);
     w.alpha1 = (float *)take((size_t)d->T_max * (d->n_const ? d->n_const : 1) * 4);
     w.counts = (int32_t *)take(N * 4);
+    w.kept = (int32_t *)take(N * 4);
     w.offsets = (int32_t *)take(((size_t)d->n_ffn + 1) * 4);
     w.row_of = (int32_t *)take(slots * 4);
     w.src_of = (int32_t *)take(slots * 4);
@@ -73,6 +79,8 @@ size_t layout(const moepp_desc *d, char *base, Workspace *ws) {
     w.h = take(d->n_ffn ? slots * d->F * elt(d) : 0);
     w.yffn = take(d->n_ffn ? slots * d->D * elt(d) : 0);
     w.wsplit = take(d->act == MOEPP_BF16 ? router_split_bytes(d->D, (int)N + 2 * d->n_const) : 0);
+    w.bal_partial = (double *)take((size_t)kBalWaves * kMaxExperts * sizeof(double));
+    w.bal = (float *)take((2 * N + 1) * 4);
     if (ws) *ws = w;
     return off;
 }
@@ -170,6 +178,7 @@ moepp_status do_route(moepp_ctx *c, hipStream_t s, int T, const void *x, const f
     if (st != MOEPP_OK) return st;
     c->last_T = T;
     c->last_k = k;
+    c->last_out_gate = out_gate;
     if (T == 0) return MOEPP_OK;
     KernelTimer kt(c, s, MOEPP_K_ROUTER);
     hipError_t e = mfma ? launch_router_mfma(a, s)
@@ -189,12 +198,17 @@ moepp_status do_permute(moepp_ctx *c, hipStream_t s, int T, int k) {
     if (e != hipSuccess) return MOEPP_EHIP;
     {
         KernelTimer kt(c, s, MOEPP_K_SCAN);
-        e = launch_perm_scan(d, c->ws, s);
+        e = launch_perm_scan(d, c->ws, c->cap, s);
     }
     if (e != hipSuccess) return MOEPP_EHIP;
     {
         KernelTimer kt(c, s, MOEPP_K_SCATTER);
-        e = launch_perm_scatter(d, c->ws, s);
+        e = launch_perm_scatter(d, c->ws, c->cap, s);
+    }
+    if (e != hipSuccess) return MOEPP_EHIP;
+    if (c->bal_tau > 0.0 && T > 0) {
+        KernelTimer kt(c, s, MOEPP_K_BALANCE);
+        e = launch_balance(d, c->ws, c->last_out_gate, (float)c->bal_tau, s);
     }
     return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
 }
@@ -295,6 +309,10 @@ moepp_status moepp_create(const moepp_desc *desc, void *workspace, size_t bytes,
     c->ws_bytes = layout(desc, (char *)workspace, &c->ws);
     c->bias = nullptr;
     c->variant = 0;
+    c->cap.on = false;
+    for (int i = 0; i < kMaxExperts; ++i) c->cap.cap[i] = 0;
+    c->bal_tau = 0.0;
+    c->last_out_gate = nullptr;
     c->last_T = 0;
     c->last_k = desc->k;
     c->timing = false;
@@ -338,6 +356,61 @@ moepp_status moepp_set_router_bias(moepp_ctx *ctx, const float *bias) {
     return MOEPP_OK;
 }
 
+moepp_status moepp_capacity(const moepp_desc *desc, int32_t T, int32_t k, double gamma, double tau,
+                            int32_t *cap_host) {
+    moepp_status st = check_desc(desc);
+    if (st != MOEPP_OK) return st;
+    if (!cap_host || T < 0 || T > desc->T_max || k < 1 || k > desc->k) return MOEPP_EINVAL;
+    if (!(gamma > 0.0) || !(tau > 0.0) || !isfinite(gamma) || !isfinite(tau)) return MOEPP_EINVAL;
+    const int N = n_experts(desc);
+    const double S = (double)T * (double)k;                     // assignments
+    const double den = tau * (double)desc->n_ffn + (double)(N - desc->n_ffn);
+    for (int i = 0; i < N; ++i) {
+        const double c = i < desc->n_ffn ? gamma * tau * S / den : gamma * S / den;
+        // rounded up; a value above an integer only by the representation
+        // error of gamma and tau counts as that integer
+        const double r = ceil(c - 1e-9 * (c > 1.0 ? c : 1.0));
+        cap_host[i] = r > 2147483647.0 ? 2147483647 : (int32_t)r;
+    }
+    return MOEPP_OK;
+}
+
+moepp_status moepp_set_capacity(moepp_ctx *ctx, const int32_t *cap_host) {
+    if (!ctx) return MOEPP_EINVAL;
+    if (!cap_host) {
+        ctx->cap.on = false;
+        return MOEPP_OK;
+    }
+    const int N = n_experts(&ctx->desc);
+    for (int i = 0; i < N; ++i)
+        if (cap_host[i] < 0) return MOEPP_EINVAL;
+    for (int i = 0; i < kMaxExperts; ++i) ctx->cap.cap[i] = i < N ? cap_host[i] : 0;
+    ctx->cap.on = true;
+    return MOEPP_OK;
+}
+
+moepp_status moepp_set_balance(moepp_ctx *ctx, double tau) {
+    if (!ctx || !(tau == tau) || !isfinite(tau)) return MOEPP_EINVAL;
+    ctx->bal_tau = tau > 0.0 ? tau : 0.0;
+    return MOEPP_OK;
+}
+
+moepp_status moepp_get_balance(moepp_ctx *ctx, const float **f, const float **P,
+                               const float **loss) {
+    if (!ctx) return MOEPP_EINVAL;
+    const int N = n_experts(&ctx->desc);
+    if (f) *f = ctx->ws.bal;
+    if (P) *P = ctx->ws.bal + N;
+    if (loss) *loss = ctx->ws.bal + 2 * N;
+    return MOEPP_OK;
+}
+
+moepp_status moepp_get_kept(moepp_ctx *ctx, const int32_t **kept) {
+    if (!ctx || !kept) return MOEPP_EINVAL;
+    *kept = ctx->ws.kept;
+    return MOEPP_OK;
+}
+
 moepp_status moepp_set_variant(moepp_ctx *ctx, int32_t variant) {
     if (!ctx || variant < 0 || variant > 2) return MOEPP_EINVAL;
     ctx->variant = variant;
@@ -359,6 +432,8 @@ moepp_status moepp_route(moepp_ctx *ctx, void *stream, int32_t T, const void *x,
 moepp_status moepp_permute(moepp_ctx *ctx, void *stream, int32_t T, int32_t k) {
     moepp_status st = check_call(ctx, T, k);
     if (st != MOEPP_OK) return st;
+    // the statistics read the logits of the routed call this permutation belongs to
+    if (ctx->bal_tau > 0.0 && T > 0 && (!ctx->last_out_gate || ctx->last_T != T)) return MOEPP_EINVAL;
     reset_ran(ctx);
     return do_permute(ctx, (hipStream_t)stream, T, k);
 }

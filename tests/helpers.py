@@ -42,12 +42,17 @@ def make_layer(shape, device="cuda:0", T_max=None):
                    shape.n_copy, shape.n_const, k=shape.k, act=shape.act, device=device)
 
 
-def gpu_forward(shape, inp, variant=0, layer=None, dev=None, intermediates=True):
-    """One moepp_layer_forward call; every output copied back as numpy."""
+def gpu_forward(shape, inp, variant=0, layer=None, dev=None, intermediates=True, cap=None,
+                balance_tau=0.0):
+    """One moepp_layer_forward call; every output copied back as numpy.
+    cap: per-expert capacities (None: unlimited); balance_tau > 0: also the
+    load-balance statistics of Eq.7."""
     import torch
     dev = dev or to_device(shape, inp)
     L = layer or make_layer(shape)
     L.set_variant(variant)
+    L.set_capacity(cap)
+    L.set_balance(balance_tau)
     packed = L.pack_experts(dev["w1"], dev["w3"], dev["w2"]) if shape.n_ffn else None
     L.set_router_bias(dev.get("bias"))
     cv = dev["const_vecs"] if shape.n_const else None
@@ -63,6 +68,10 @@ def gpu_forward(shape, inp, variant=0, layer=None, dev=None, intermediates=True)
         return res
     for k, v in L.get_routing().items():
         res[k] = v.cpu().numpy().copy()
+    res["kept"] = L.get_kept().cpu().numpy().copy()
+    if balance_tau > 0:
+        for k, v in L.get_balance().items():
+            res[k] = v.cpu().numpy().astype(np.float64)
     if intermediates:
         R = int(res["offsets"][-1]) if shape.n_ffn else 0
         for k, v in L.get_intermediates(R).items():
@@ -101,9 +110,10 @@ def reconcile_routing(shape, inp, res):
     return r, int(diff.size)
 
 
-def check_layer(shape, inp, res, tok_list=None, max_near_ties=None, check_inter=True):
+def check_layer(shape, inp, res, tok_list=None, max_near_ties=None, check_inter=True, cap=None,
+                balance_tau=0.0):
     """Compare one GPU forward with the oracle.  Returns a dict of measured
-    errors (for reporting)."""
+    errors (for reporting).  cap / balance_tau as given to gpu_forward."""
     s = shape
     r, near = reconcile_routing(s, inp, res)
     if max_near_ties is None:
@@ -116,8 +126,15 @@ def check_layer(shape, inp, res, tok_list=None, max_near_ties=None, check_inter=
     assert e_gate <= TOL_F32, "out_gate rel err %g" % e_gate
     assert e_w <= TOL_F32, "topk_w rel err %g" % e_w
     # permutation: bit-exact
-    p = oracle.permute(s, r["topk_idx"])
+    if cap is None:
+        p = oracle.permute(s, r["topk_idx"])
+        p["kept"] = p["counts"]
+        row_of = None
+    else:
+        p = oracle.permute_capacity(s, r["topk_idx"], cap)
+        row_of = p["row_of"]
     R = int(p["offsets"][-1])
+    assert np.array_equal(res["kept"], p["kept"])
     assert np.array_equal(res["counts"], p["counts"])
     assert np.array_equal(res["offsets"], p["offsets"])
     assert np.array_equal(res["row_of"], p["row_of"])
@@ -126,11 +143,19 @@ def check_layer(shape, inp, res, tok_list=None, max_near_ties=None, check_inter=
     # outputs
     want = dict(want_slots=check_inter, want_h=check_inter, want_alpha=True)
     o = oracle.experts(s, inp["x"], r["topk_idx"], r["topk_w"], inp["w1"], inp["w3"],
-                       inp["w2"], inp["const_vecs"], inp["W_c"], tok_list=tok_list, **want)
+                       inp["w2"], inp["const_vecs"], inp["W_c"], tok_list=tok_list,
+                       row_of=row_of, **want)
     toks = np.arange(s.T) if tok_list is None else np.asarray(tok_list)
     e_out = rel_err(res["out"][toks], o["out"])
     assert e_out <= TOL_OUT[s.act], "out rel err %g > %g" % (e_out, TOL_OUT[s.act])
-    errs = {"out": e_out, "out_gate": e_gate, "topk_w": e_w, "near_ties": near, "R": R}
+    errs = {"out": e_out, "out_gate": e_gate, "topk_w": e_w, "near_ties": near, "R": R,
+            "dropped": int(s.T * s.k - p["kept"].sum())}
+    if balance_tau > 0:
+        b = oracle.balance(s, r["probs"], r["topk_idx"], balance_tau)
+        assert np.array_equal(res["f"], b["f"].astype(np.float32))      # counts / T, one rounding
+        errs["P"] = rel_err(res["P"], b["P"])
+        errs["loss"] = abs(float(res["loss"][0]) - b["loss"]) / abs(b["loss"])
+        assert errs["P"] <= TOL_F32 and errs["loss"] <= TOL_F32, errs
     if s.n_const and "alpha1" in res:
         e_a = rel_err(res["alpha1"][toks], o["alpha1"])
         assert e_a <= TOL_F32, "alpha1 rel err %g" % e_a

@@ -188,3 +188,49 @@ def test_mfma_ceiling_argument_checks(L):
     assert L.moepp_mfma_ceiling(None, fake(), 1 << 20, 0, byref(flops)) == B.EINVAL
     assert L.moepp_mfma_ceiling(None, fake(), 1 << 20, 100, None) == B.EINVAL
     assert L.moepp_mfma_ceiling(None, fake(), 1024, 100, byref(flops)) == B.ENOMEM
+
+
+def test_capacity_is_host_arithmetic_and_matches_the_oracle(L):
+    """moepp_capacity needs no GPU; Eq.8 in the library and in the oracle are
+    two independent implementations of the same formula."""
+    import oracle
+    from types import SimpleNamespace as NS
+    for T, k, nf, nz, nc, nk, gamma, tau in [(256, 2, 4, 1, 1, 2, 1.1, 0.75), (100, 2, 8, 4, 0, 0, 1.1, 0.75),
+                                             (32768, 2, 16, 1, 1, 2, 1.1, 0.75), (7, 3, 5, 1, 1, 0, 1.0, 0.1),
+                                             (1000, 4, 1, 3, 2, 2, 2.0, 0.25), (33, 1, 3, 0, 0, 0, 2.0, 1.0),
+                                             (1, 1, 1, 1, 0, 0, 1.0, 1.0), (0, 2, 4, 1, 1, 2, 1.1, 0.75)]:
+        d = desc(T_max=max(T, 1), n_ffn=nf, n_zero=nz, n_copy=nc, n_const=nk, k=k)
+        N = nf + nz + nc + nk
+        cap = (ctypes.c_int32 * N)()
+        assert L.moepp_capacity(byref(d), T, k, gamma, tau, cap) == B.OK
+        sh = NS(T=T, D=64, F=96, n_ffn=nf, n_zero=nz, n_copy=nc, n_const=nk, k=k)
+        assert list(cap) == oracle.capacity(sh, gamma, tau).tolist(), (T, k, nf, gamma, tau)
+
+
+def test_capacity_and_balance_argument_checks(L, ctx):
+    d = desc()
+    cap = (ctypes.c_int32 * 8)()
+    assert L.moepp_capacity(None, 16, 2, 1.1, 0.75, cap) == B.EINVAL
+    assert L.moepp_capacity(byref(d), 16, 2, 1.1, 0.75, None) == B.EINVAL
+    assert L.moepp_capacity(byref(d), 129, 2, 1.1, 0.75, cap) == B.EINVAL      # > T_max
+    assert L.moepp_capacity(byref(d), 16, 3, 1.1, 0.75, cap) == B.EINVAL       # > desc.k
+    assert L.moepp_capacity(byref(d), 16, 2, 0.0, 0.75, cap) == B.EINVAL
+    assert L.moepp_capacity(byref(d), 16, 2, 1.1, -1.0, cap) == B.EINVAL
+    assert L.moepp_capacity(byref(d), 16, 2, float("nan"), 0.75, cap) == B.EINVAL
+    assert L.moepp_set_capacity(None, cap) == B.EINVAL
+    bad = (ctypes.c_int32 * 8)(1, 2, -1, 4, 5, 6, 7, 8)
+    assert L.moepp_set_capacity(ctx, bad) == B.EINVAL
+    assert L.moepp_set_capacity(ctx, cap) == B.OK
+    assert L.moepp_set_capacity(ctx, None) == B.OK
+    assert L.moepp_set_balance(None, 0.5) == B.EINVAL
+    assert L.moepp_set_balance(ctx, float("inf")) == B.EINVAL
+    assert L.moepp_set_balance(ctx, 0.75) == B.OK
+    # statistics are on: a permutation needs the routed call it belongs to
+    assert L.moepp_permute(ctx, None, 16, 2) == B.EINVAL
+    assert L.moepp_set_balance(ctx, 0.0) == B.OK
+    p = [c_void_p() for _ in range(3)]
+    assert L.moepp_get_balance(ctx, *[byref(q) for q in p]) == B.OK
+    assert all(q.value for q in p)
+    k = c_void_p()
+    assert L.moepp_get_kept(ctx, byref(k)) == B.OK and k.value
+    assert L.moepp_get_kept(ctx, None) == B.EINVAL

@@ -102,6 +102,66 @@ def test_fp32_layers_all_tokens(kw):
     say("errs", check_layer(s, inp, res))
 
 
+# ------------------------------------------- expert capacity, load balance
+@pytest.mark.parametrize("variant", [1, 0])
+@pytest.mark.parametrize("kw,gamma,tau", [
+    (dict(T=1000, D=256, F=384, n_ffn=6, seed=101), 1.1, 0.75),      # the paper's defaults
+    (dict(T=777, D=256, F=128, n_ffn=4, n_zero=2, n_copy=2, n_const=4, k=4, seed=102), 0.5, 0.25),
+    (dict(T=600, D=128, F=128, n_ffn=8, n_zero=0, n_copy=0, n_const=0, seed=103), 0.8, 1.0),
+    (dict(T=300, D=256, F=256, bias="normal", seed=104), 1.0, 0.1),
+])
+def test_expert_capacity_and_balance_statistics(kw, gamma, tau, variant):
+    s = small_shape("cap", **kw)
+    inp = make_inputs(s)
+    L = make_layer(s)
+    cap = L.capacity(s.T, gamma, tau)
+    assert cap == oracle.capacity(s, gamma, tau).tolist()
+    say("capacity", kw, gamma, tau, cap, "variant", variant)
+    res = gpu_forward(s, inp, variant=variant, layer=L, cap=cap, balance_tau=tau)
+    errs = check_layer(s, inp, res, cap=np.array(cap, np.int32), balance_tau=tau)
+    say("errs", errs)
+    assert errs["dropped"] > 0
+    assert np.all(res["kept"] <= np.array(cap))
+    # switching the capacities off again restores the unlimited layer
+    res2 = gpu_forward(s, inp, variant=variant, layer=L)
+    check_layer(s, inp, res2)
+    assert (res2["row_of"] != -2).all()
+
+
+def test_capacity_extremes():
+    s = small_shape("cap0", T=200, n_ffn=4)
+    inp = make_inputs(s)
+    L = make_layer(s)
+    # nothing fits anywhere: every slot is dropped, the layer outputs zero
+    res = gpu_forward(s, inp, layer=L, cap=[0] * s.N)
+    assert (res["row_of"] == -2).all() and res["offsets"][-1] == 0 and not res["kept"].any()
+    assert not res["out"].any()
+    check_layer(s, inp, res, cap=np.zeros(s.N, np.int32))
+    # capacities nobody reaches change nothing; a single place in one expert
+    big = [s.T * s.k] * s.N
+    check_layer(s, inp, gpu_forward(s, inp, layer=L, cap=big), cap=np.array(big, np.int32))
+    one = list(big)
+    one[0] = 1
+    r1 = gpu_forward(s, inp, layer=L, cap=one)
+    check_layer(s, inp, r1, cap=np.array(one, np.int32))
+    assert r1["kept"][0] == 1 and r1["counts"][0] > 1
+
+
+def test_workload_mid_with_the_papers_capacity_sampled():
+    """Ragged groups (router bias) at gamma = 1.1, tau = 0.75: the large groups are cut."""
+    s = WORKLOADS["mid"]
+    inp = make_inputs(s)
+    L = make_layer(s)
+    cap = L.capacity(s.T, 1.1, 0.75)
+    assert cap == oracle.capacity(s, 1.1, 0.75).tolist()
+    res = gpu_forward(s, inp, variant=2, layer=L, cap=cap, balance_tau=0.75, intermediates=False)
+    toks = sample_tokens(s, res["topk_idx"], 256, seed=9)
+    errs = check_layer(s, inp, res, tok_list=toks, cap=np.array(cap, np.int32), balance_tau=0.75,
+                       check_inter=False)
+    say("mid with capacity", errs, "kept", res["kept"].tolist())
+    assert errs["dropped"] > 0
+
+
 # ------------------------------------------------------------------ edge cases
 @pytest.mark.parametrize("variant", [1, 0])
 def test_edge_routing_patterns(variant):
@@ -215,7 +275,7 @@ def test_step_calls_equal_the_fused_call_and_timing_reports():
                     dev["const_vecs"], dev["W_c"])
     ms = L.get_timing()
     say("kernel ms", ms)
-    assert all(v > 0 for v in ms.values())
+    assert all(v > 0 for k, v in ms.items() if k != "balance") and ms["balance"] == 0   # statistics are off
     L.set_timing(False)
 
 
