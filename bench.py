@@ -86,6 +86,52 @@ def run_gpu(shape, inp, steps, warmup, capacity=None):
     return res
 
 
+def run_chain(shape, inp, n_layers, steps, warmup):
+    """n_layers layers back to back (the same weights, G(x^j) of one layer is the
+    gating residual input of the next, Eq.6; the first has none), eagerly and as one
+    HIP graph: what the launch overhead of the seven kernels per layer costs."""
+    import torch
+    from helpers import make_layer, to_device
+    dev = to_device(shape, inp)
+    L = make_layer(shape)
+    packed = L.pack_experts(dev["w1"], dev["w3"], dev["w2"]) if shape.n_ffn else None
+    L.set_router_bias(dev.get("bias"))
+    cv = dev["const_vecs"] if shape.n_const else None
+    wc = dev["W_c"] if shape.n_const else None
+    out = torch.empty((shape.T, shape.D), dtype=L.act_dtype, device=L.device)
+    gates = [torch.empty((shape.T, shape.N), dtype=torch.float32, device=L.device) for _ in range(2)]
+
+    def chain():
+        for j in range(n_layers):
+            L.layer_forward(dev["x"], gates[(j - 1) % 2] if j else None, dev["W_g"],
+                            dev["W_res"] if j else None, packed, cv, wc, k=shape.k, out=out,
+                            out_gate=gates[j % 2])
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    eager = timed(chain)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        chain()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            chain()
+    torch.cuda.current_stream().wait_stream(side)
+    replay = timed(graph.replay)
+    return {"layers": n_layers, "eager_ms_per_layer": eager / n_layers,
+            "graph_ms_per_layer": replay / n_layers}
+
+
 def roofline_numbers(shape, g):
     """Algorithmic work per launch / measured duration, per kernel."""
     T, D, F, N, K, R = shape.T, shape.D, shape.F, shape.N, shape.k, g["R"]
@@ -152,6 +198,8 @@ def main():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--no-vanilla", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chain", type=int, default=0,
+                    help="also time this many layers back to back, eagerly and as one HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the layer on one GPU only; --gpus %d is not "
@@ -258,6 +306,13 @@ def main():
         log("with capacity", result["with_capacity"])
         del gc
         torch.cuda.empty_cache()
+
+    if args.chain > 0 and shape.residual:
+        for k_ in ("layer", "dev", "out"):
+            g.pop(k_, None)
+        torch.cuda.empty_cache()
+        result["chain"] = run_chain(shape, inp, args.chain, args.steps, args.warmup)
+        log("chain", result["chain"])
 
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a sample")
