@@ -1,4 +1,5 @@
-// Grouped SwiGLU FFN on the bf16 matrix cores (gfx950, v_mfma_f32_32x32x16_bf16).
+// Grouped SwiGLU FFN on the bf16 matrix cores (gfx950, v_mfma_f32_16x16x32_bf16 by
+// default, v_mfma_f32_32x32x16_bf16 as an option).
 //
 // For every FFN expert e and the rows r of its group (paper Eq.2: the FFN
 // experts of the layer; group sizes are ragged, they follow the routing):
@@ -59,8 +60,12 @@ typedef __attribute__((address_space(3))) void *lptr_t;
 // Tile geometry.  BK K-elements per LDS stage; NS stages form a ring, NS - 1
 // tiles are in flight (or being computed) at any time.
 // LW_ of the WM*WN waves issue the tile loads (0: all of them).
-template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int LW_ = 0, bool PERSIST_ = false>
+// MI_: edge of the MFMA block, 32 (v_mfma_f32_32x32x16_bf16) or 16 (v_mfma_f32_16x16x32_bf16).
+template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int LW_ = 0, bool PERSIST_ = false,
+          int MI_ = 32>
 struct Geo {
+    static constexpr int MI = MI_;
+    static_assert(MI_ == 32 || (MI_ == 16 && BK_ == 32 && NS_ >= 3), "16x16x32 blocks: one MFMA K step per 32-deep stage, ring path");
     static constexpr bool PERSIST = PERSIST_;          // one workgroup per CU runs tile after tile
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
     static constexpr int NT = WM * WN * kWave;         // threads
@@ -269,7 +274,14 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     const int a_base = (wm * TM) * RB;
     const int b_base = BM * RB + (wn * TN) * RB;
 
-    f32x16 acc[NB][MB];
+    // accumulators: 32x32 blocks of 16 registers, or 16x16 blocks of 4
+    constexpr int MI = G::MI;
+    constexpr int NBX = TN / MI, MBX = TM / MI;
+    typedef typename std::conditional<MI == 32, f32x16, f32x4>::type acc_t;
+    acc_t acc[NBX][MBX];
+    // 16x16x32 blocks: lane l reads row (l % 16) of a 16-row block, 16-byte chunk l / 16 of its 64-byte row
+    const int l16 = lane % 16, lq = lane / 16;
+    const int rd16 = l16 * RB + ((lq ^ G::swz(l16)) << 4);
 
     auto read_frags = [&](const char *st, int ks, bf16x8 *fa, bf16x8 *fb) {
 #pragma unroll
@@ -279,12 +291,17 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         for (int j = 0; j < NB; ++j)
             fb[j] = *reinterpret_cast<const bf16x8 *>(st + b_base + j * 32 * RB + rd_off[ks]);
     };
+    auto mfma32 = [&](bf16x8 b, bf16x8 a_, auto &c) {
+        if constexpr (MI == 32) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a_, c, 0, 0, 0);
+    };
+    auto mfma16 = [&](bf16x8 b, bf16x8 a_, auto &c) {
+        if constexpr (MI == 16) c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, a_, c, 0, 0, 0);
+    };
     auto mfma_step = [&](const bf16x8 *fa, const bf16x8 *fb) {
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
-            for (int i = 0; i < MB; ++i)
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[j][i], 0, 0, 0);
+            for (int i = 0; i < MB; ++i) mfma32(fb[j], fa[i], acc[j][i]);
     };
     // One K step with its memory operations spread evenly between the MFMAs:
     // first the operand reads of the NEXT step (from `st`, step `ks_rd`, into
@@ -300,7 +317,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int i = 0; i < MB; ++i) {
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[j][i], 0, 0, 0);
+                mfma32(fb[j], fa[i], acc[j][i]);
                 const int idx = j * MB + i;
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -432,6 +449,117 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         }
     };
 
+    // ---- the same K loop with 16x16x32 MFMA blocks ----------------------------
+    // Measured on register operands with random data (the chip is power limited
+    // there), v_mfma_f32_16x16x32_bf16 sustains 2130 TFLOP/s where
+    // v_mfma_f32_32x32x16_bf16 sustains 1870: a quarter of the accumulator
+    // registers move per instruction for half of the flops.  One MFMA covers
+    // the whole 32-deep K tile, so the two phases of a tile are the two halves
+    // of the wave's rows: phase 0 multiplies A blocks 0 .. MBH-1 with every B
+    // block, phase 1 the other MBH.  The barrier sits before phase 1; during
+    // phase 0 the A operands of phase 1 are read, during phase 1 the B
+    // operands and the first A operands of the next tile (B is double
+    // buffered in registers; tiles come in pairs so that the buffer index is a
+    // compile-time constant: K % 64 == 0 makes the number of tiles even).
+    auto main_loop16 = [&](auto loader_c) {
+        constexpr bool LOADER = decltype(loader_c)::value;
+        constexpr int NB16 = TN / 16, MBH = TM / 32;          // B blocks; A blocks per phase
+        constexpr int SLOTS = NB16 * MBH;                      // MFMAs per phase
+        constexpr int L0 = LPT - LPT / 2, L1 = LPT / 2;        // tile loads issued in phase 0 / phase 1
+        static_assert(MBH + L0 <= SLOTS && NB16 + MBH + L1 <= SLOTS, "one memory operation per MFMA");
+        bf16x8 fa[2][MBH], fb[2][NB16];
+        auto read_a = [&](const char *__restrict__ st, int blk) {
+            return *reinterpret_cast<const bf16x8 *>(st + a_base + blk * 16 * RB + rd16);
+        };
+        auto read_b = [&](const char *__restrict__ st, int blk) {
+            return *reinterpret_cast<const bf16x8 *>(st + b_base + blk * 16 * RB + rd16);
+        };
+        // one phase: SLOTS MFMAs, after each at most one read or tile load
+        auto phase = [&](auto ph_c, auto par_c, auto read_c, auto n_load_c, const char *__restrict__ st,
+                         int kt_issue, char *__restrict__ wr) {
+            constexpr int PH = decltype(ph_c)::value, P = decltype(par_c)::value;
+            constexpr bool READ = decltype(read_c)::value;
+            constexpr int N_LOAD = decltype(n_load_c)::value;
+            constexpr int N_READ = PH == 0 ? MBH : NB16 + MBH;
+            constexpr int OPS = N_READ + N_LOAD;
+#pragma unroll
+            for (int j = 0; j < NB16; ++j)
+#pragma unroll
+                for (int i = 0; i < MBH; ++i) {
+                    mfma16(fb[P][j], fa[PH][i], acc[j][PH * MBH + i]);
+                    const int idx = j * MBH + i;
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int o = 0; o < OPS; ++o) {
+                        if (o * SLOTS / OPS != idx) continue;
+                        if (o >= N_READ) {
+                            issue_one((PH == 0 ? 0 : L0) + o - N_READ, kt_issue, wr);
+                        } else if (READ) {
+                            if (PH == 0) fa[1][o] = read_a(st, MBH + o);          // this tile, phase 1
+                            else if (o < NB16) fb[1 - P][o] = read_b(st, o);       // next tile
+                            else fa[0][o - NB16] = read_a(st, o - NB16);           // next tile, phase 0
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        };
+        typedef std::true_type yes_t;
+        typedef std::false_type no_t;
+        // One tile.  cur / nxt / wr are three different stages (restrict).
+        auto k_tile = [&](auto par_c, const char *__restrict__ cur, const char *__restrict__ nxt,
+                          char *__restrict__ wr, int kt_issue, auto vm_c, auto issue_c, auto last_c) {
+            constexpr int VM = decltype(vm_c)::value;
+            constexpr bool ISSUE = decltype(issue_c)::value, LAST = decltype(last_c)::value;
+            typedef std::integral_constant<int, ISSUE && LOADER ? L0 : 0> l0_t;
+            typedef std::integral_constant<int, ISSUE && LOADER ? L1 : 0> l1_t;
+            __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): operands read during the previous phase
+            __builtin_amdgcn_sched_barrier(0);
+            phase(std::integral_constant<int, 0>{}, par_c, yes_t{}, l0_t{}, cur, kt_issue, wr);
+            if constexpr (!LAST) wait_and_barrier<VM>();   // tile kt+1 landed; my reads of tile kt complete
+            else __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_sched_barrier(0);
+            phase(std::integral_constant<int, 1>{}, par_c, std::integral_constant<bool, !LAST>{}, l1_t{},
+                  nxt, kt_issue, wr);
+        };
+        int s_cur = S0, s_nxt = (S0 + 1) % NS, s_wr = (S0 + NS - 1) % NS;
+        auto rotate = [&]() {
+            s_wr = s_cur;
+            s_cur = s_nxt;
+            s_nxt = s_nxt + 1 == NS ? 0 : s_nxt + 1;
+        };
+        wait_and_barrier<(NS - 2) * LPT>();     // tile 0 landed
+#pragma unroll
+        for (int j = 0; j < NB16; ++j) fb[0][j] = read_b(lds + S0 * STAGE, j);
+#pragma unroll
+        for (int i = 0; i < MBH; ++i) fa[0][i] = read_a(lds + S0 * STAGE, i);
+        typedef std::integral_constant<int, (NS - 3) * LPT + L0> vm_steady_t;
+        typedef std::integral_constant<int, 0> par0_t;
+        typedef std::integral_constant<int, 1> par1_t;
+        // KT is even and NS - 1 = 4 tiles are peeled: the steady tiles come in pairs
+        static_assert(NS == 5, "pairing of the tiles assumes an even number of peeled tiles");
+        for (int kt = 0; kt < KT - (NS - 1); kt += 2) {
+            k_tile(par0_t{}, lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, kt + NS - 1,
+                   vm_steady_t{}, yes_t{}, no_t{});
+            rotate();
+            k_tile(par1_t{}, lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, kt + NS,
+                   vm_steady_t{}, yes_t{}, no_t{});
+            rotate();
+        }
+        // the last NS-1 tiles: nothing left to issue, fewer loads in flight
+        auto tail = [&](auto t_c) {
+            constexpr int t = decltype(t_c)::value;
+            constexpr int younger = NS - 3 - t > 0 ? NS - 3 - t : 0;
+            k_tile(std::integral_constant<int, t % 2>{}, lds + s_cur * STAGE, lds + s_nxt * STAGE,
+                   lds + s_wr * STAGE, 0, std::integral_constant<int, younger * LPT>{}, no_t{},
+                   std::integral_constant<bool, t == NS - 2>{});
+            rotate();
+        };
+        tail(std::integral_constant<int, 0>{});
+        tail(std::integral_constant<int, 1>{});
+        tail(std::integral_constant<int, 2>{});
+        tail(std::integral_constant<int, 3>{});
+    };
+
     // ---- epilogue: registers -> LDS patch -> 16-byte stores --------------------
     // acc[j][i][v]: output row m = wm*TM + i*32 + l32,
     //               B row n = wn*TN + j*32 + 8*(v/4) + 4*lh + v%4
@@ -452,6 +580,38 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         for (int ep = 0; ep < EP; ++ep) {
             if (ep > 0) lds_sync();                    // the previous pass has left the patch
             if ((wm * TM) / HB == ep) {
+                if constexpr (MI == 16) {
+                    // 16x16 blocks: acc[j][i][v] is output row wm*TM + i*16 + l16,
+                    // B row wn*TN + j*16 + 4*lq + v; B rows come in blocks of 32
+                    // rows of W1 then 32 rows of W3 (GEMM1), so 16-row block j
+                    // pairs with block j + 2
+#pragma unroll
+                    for (int i = 0; i < MBX; ++i) {
+                        const int m = wm * TM + i * 16 + l16 - ep * HB;
+                        char *orow = patch + m * OUT_STRIDE;
+                        if constexpr (SWIGLU) {
+#pragma unroll
+                            for (int jp = 0; jp < NBX / 2; ++jp) {
+                                const int jg = (jp / 2) * 4 + jp % 2;             // silu's argument
+                                const int c0 = (wn * TN) / 2 + (jp / 2) * 32 + (jp % 2) * 16 + 4 * lq;
+                                bf16x4 o;
+#pragma unroll
+                                for (int q = 0; q < 4; ++q)
+                                    o[q] = (bf16_t)(fast_silu(acc[jg][i][q]) * acc[jg + 2][i][q]);
+                                *reinterpret_cast<bf16x4 *>(orow + c0 * 2) = o;
+                            }
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < NBX; ++j) {
+                                const int c0 = wn * TN + j * 16 + 4 * lq;
+                                bf16x4 o;
+#pragma unroll
+                                for (int q = 0; q < 4; ++q) o[q] = (bf16_t)acc[j][i][q];
+                                *reinterpret_cast<bf16x4 *>(orow + c0 * 2) = o;
+                            }
+                        }
+                    }
+                } else {
 #pragma unroll
                 for (int i = 0; i < MB; ++i) {
                     const int m = wm * TM + i * 32 + l32 - ep * HB;
@@ -482,6 +642,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
                             }
                         }
                     }
+                }
                 }
             }
             lds_sync();
@@ -536,12 +697,13 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
                 if constexpr (LOADER) gather_rows(n_row0, n_row_end, src);
             }
 #pragma unroll
-            for (int jj = 0; jj < NB; ++jj)
+            for (int jj = 0; jj < NBX; ++jj)
 #pragma unroll
-                for (int i = 0; i < MB; ++i)
+                for (int i = 0; i < MBX; ++i)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[jj][i][v] = 0.f;
-            main_loop(loader_c);
+                    for (int v = 0; v < (int)(sizeof(acc_t) / sizeof(float)); ++v) acc[jj][i][v] = 0.f;
+            if constexpr (MI == 16) main_loop16(loader_c);
+            else main_loop(loader_c);
             __syncthreads();                    // all waves done reading the stages
             if constexpr (!G::PERSIST) {
                 epilogue(lds, lds, std::integral_constant<int, 0>{});
@@ -630,11 +792,12 @@ static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
 hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
     if (f.d.T == 0 || f.d.n_ffn == 0) return hipSuccess;
     // Default: 256x256 tile, 8 waves of which the first 4 issue the tile loads,
-    // 32-deep K stages in a ring of 5 (the whole 160 KB of LDS), which needs
-    // at least 4 K tiles; shorter reductions use two 64-deep stages.
+    // 16x16x32 MFMA blocks, persistent workgroups, 32-deep K stages in a ring
+    // of 5 (the whole 160 KB of LDS), which needs at least 4 K tiles; shorter
+    // reductions use two 64-deep stages.
     // MOEPP_GEMM_CFG selects other geometries, for tuning: 1 = 4 waves with
     // 128x128 wave tiles, 2 = ring of 3, 3 = two 64-deep stages, 5 = every
-    // wave loads, 7 = 128-row tiles.
+    // wave loads, 6 = 32x32x16 MFMA blocks, 7 = 128-row tiles.
     const char *v = getenv("MOEPP_GEMM_CFG");
     int cfg = v ? atoi(v) : 0;
     const int K = which == 0 ? f.d.D : f.d.F;
@@ -649,7 +812,8 @@ hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
         case 3: return launch_cfg<Geo<256, 256, 2, 4, 64, 2>>(f, which, s);
         case 5: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);
         case 7: return launch_cfg<Geo<128, 256, 1, 4, 32, 5, 0, true>>(f, which, s);
-        default: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true>>(f, which, s);
+        case 6: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true>>(f, which, s);
+        default: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true, 16>>(f, which, s);
     }
 }
 
