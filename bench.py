@@ -132,6 +132,45 @@ def run_chain(shape, inp, n_layers, steps, warmup):
             "graph_ms_per_layer": replay / n_layers}
 
 
+def tau_sweep(model, steps, warmup):
+    """Expert-forward time of one layer of a paper model (Tab.2 shape) against tau, with
+    the expert capacities of Eq.8 and a router bias under which the zero-computation
+    experts take N_ZC / (tau N_FFN + N_ZC) of the assignments, next to the vanilla MoE
+    layer with the same FFN experts: the shape of the paper's Tab.3 on this GPU."""
+    import torch
+    from workloads import PAPER_MODELS, make_inputs
+    base = PAPER_MODELS[model]
+    rows = []
+    van = base.with_(name=base.name + "_vanilla", n_zero=0, n_copy=0, n_const=0)
+    gv = run_gpu(van, make_inputs(van), steps, warmup)
+    kv = gv["kernel_ms"]
+    t_van = kv["gemm1"] + kv["gemm2"] + kv["combine"]
+    van_layer = gv["ms_per_step"]
+    del gv
+    torch.cuda.empty_cache()
+    for tau in (0.1, 0.25, 0.5, 0.75, 1.0):
+        s = base.with_(bias="tau%g" % tau)
+        g = run_gpu(s, make_inputs(s), steps, warmup, capacity=(1.1, tau))
+        k = g["kernel_ms"]
+        t = k["gemm1"] + k["gemm2"] + k["combine"]
+        slots = s.T * s.k
+        rows.append({"tau": tau, "expert_forward_ms": t, "layer_ms": g["ms_per_step"],
+                     "ffn_rows_fraction": g["R"] / slots,
+                     "tab1_fraction": tau * s.n_ffn / (tau * s.n_ffn + s.n_zc),
+                     "dropped_fraction": 1.0 - sum(g["kept"]) / slots,
+                     "expert_throughput_increase_pct": 100.0 * (t_van / t - 1.0),
+                     "layer_throughput_increase_pct": 100.0 * (van_layer / g["ms_per_step"] - 1.0)})
+        log("tau", rows[-1])
+        del g
+        torch.cuda.empty_cache()
+    return {"model": model, "T": base.T, "D": base.D, "F": base.F, "n_ffn": base.n_ffn,
+            "n_zc": base.n_zc, "gamma": 1.1, "vanilla_expert_forward_ms": t_van,
+            "vanilla_layer_ms": van_layer, "rows": rows,
+            "paper_context": "Tab.3 (other hardware, whole models): 1B/(16+4)E expert-forward "
+                             "throughput +111 % / +59 % / +30 % / +22 % / +15 % at tau = 0.1 / "
+                             "0.25 / 0.5 / 0.75 / 1"}
+
+
 def roofline_numbers(shape, g):
     """Algorithmic work per launch / measured duration, per kernel."""
     T, D, F, N, K, R = shape.T, shape.D, shape.F, shape.N, shape.k, g["R"]
@@ -198,6 +237,8 @@ def main():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--no-vanilla", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tau-sweep", default="",
+                    help="also time a paper model's layer (e.g. '1B/(16+4)E') against tau")
     ap.add_argument("--chain", type=int, default=0,
                     help="also time this many layers back to back, eagerly and as one HIP graph")
     args = ap.parse_args()
@@ -306,6 +347,12 @@ def main():
         log("with capacity", result["with_capacity"])
         del gc
         torch.cuda.empty_cache()
+
+    if args.tau_sweep:
+        for k_ in ("layer", "dev", "out"):
+            g.pop(k_, None)
+        torch.cuda.empty_cache()
+        result["tau_sweep"] = tau_sweep(args.tau_sweep, args.steps, args.warmup)
 
     if args.chain > 0 and shape.residual:
         for k_ in ("layer", "dev", "out"):

@@ -10,10 +10,10 @@ the hidden sizes the benchmark configurations name.  All random numbers come
 from numpy's counter-based Philox generator, one independent stream per
 tensor, so a tensor's bytes depend only on (seed, tensor name, shape).
 """
-from .gen import (LayerShape, WORKLOADS, make_inputs, make_router_bias,
+from .gen import (LayerShape, WORKLOADS, PAPER_MODELS, make_inputs, make_router_bias,
                   skew_bias_gaussian_model, round_to_bf16, TENSOR_IDS,
                   ffn_work_fraction, n_const_rule)
 
-__all__ = ["LayerShape", "WORKLOADS", "make_inputs", "make_router_bias",
+__all__ = ["LayerShape", "WORKLOADS", "PAPER_MODELS", "make_inputs", "make_router_bias",
            "skew_bias_gaussian_model", "round_to_bf16", "TENSOR_IDS",
            "ffn_work_fraction", "n_const_rule"]

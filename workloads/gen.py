@@ -27,7 +27,7 @@ class LayerShape:
     k: int = 2             # top-k, 2 in every layer of the paper (Sec. 4.1)
     act: str = "bf16"      # activation / expert-weight type: "bf16" or "f32"
     residual: bool = True  # gating residual on (layer index j > 1, Eq.6)
-    bias: str = "none"     # "none" | "normal" (N(0, 0.5) per expert) | "skew"
+    bias: str = "none"     # "none" | "normal" (N(0, 0.5) per expert) | "skew" | "tau<value>"
     seed: int = 20241007
 
     @property
@@ -66,6 +66,24 @@ WORKLOADS = {
                        n_copy=1, n_const=2, bias="skew", seed=1005),
     "smallbatch": LayerShape("smallbatch", T=64, D=4096, F=5632, n_ffn=16,
                              n_zero=1, n_copy=1, n_const=2, seed=1006),
+}
+
+# Layer shapes of the paper's models (Tab.2): hidden 768 / intermediate 2048
+# with 8, 16 or 32 FFN experts, hidden 1536 / intermediate 4096 with 16; zero /
+# copy / constant experts 1/1/2 (1/1/6 with 32 FFN experts).  16 sequences of
+# 2048 tokens (the paper's sequence length).  Used by bench.py --tau-sweep with
+# bias = "tau<value>": the zero-computation experts get a common offset under
+# which they take N_ZC / (tau N_FFN + N_ZC) of the assignments, the share the
+# heterogeneous load-balance loss steers a trained model to (Sec. 3.3, Tab.1).
+PAPER_MODELS = {
+    "0.6B/(8+4)E": LayerShape("paper_0.6b", T=16 * 2048, D=768, F=2048, n_ffn=8, n_zero=1,
+                              n_copy=1, n_const=2, seed=1010),
+    "1B/(16+4)E": LayerShape("paper_1b", T=16 * 2048, D=768, F=2048, n_ffn=16, n_zero=1,
+                             n_copy=1, n_const=2, seed=1011),
+    "2B/(32+8)E": LayerShape("paper_2b", T=16 * 2048, D=768, F=2048, n_ffn=32, n_zero=1,
+                             n_copy=1, n_const=6, seed=1012),
+    "7B/(16+4)E": LayerShape("paper_7b", T=16 * 2048, D=1536, F=4096, n_ffn=16, n_zero=1,
+                             n_copy=1, n_const=2, seed=1013),
 }
 
 # One Philox stream per tensor: key = (seed, TENSOR_IDS[name] [+ expert index]).
@@ -157,6 +175,14 @@ def make_router_bias(shape: LayerShape):
         b = np.zeros(s.N, dtype=np.float32)
         b[s.n_ffn:] = b_zc
         b[0] = b_hot
+        return b
+    if s.bias.startswith("tau"):
+        tau = float(s.bias[3:])
+        share = s.n_zc / (tau * s.n_ffn + s.n_zc)
+        b_zc, _ = skew_bias_gaussian_model(s.D, s.n_ffn, s.n_zc, s.k, s.residual, s.seed,
+                                           zc_share=share, hot_ratio=1.0)
+        b = np.zeros(s.N, dtype=np.float32)
+        b[s.n_ffn:] = b_zc
         return b
     raise ValueError(s.bias)
 
