@@ -217,8 +217,10 @@ moepp_status moepp_get_intermediates(moepp_ctx *ctx, const float **alpha1,
  */
 enum {
     MOEPP_K_ROUTER = 0,  /* router GEMM + residual + softmax + top-k         */
-    MOEPP_K_HIST = 1,    /* permute: per-chunk histogram                      */
-    MOEPP_K_SCAN = 2,    /* permute: exclusive scan                           */
+    MOEPP_K_HIST = 1,    /* permute: per-chunk histogram (0 for calls with at most
+                            4096 slots: one kernel does all three steps and is
+                            reported as MOEPP_K_SCATTER)                      */
+    MOEPP_K_SCAN = 2,    /* permute: exclusive scan (0 for such calls)        */
     MOEPP_K_SCATTER = 3, /* permute: stable scatter                           */
     MOEPP_K_GEMM1 = 4,   /* grouped GEMM W1/W3 + SwiGLU                       */
     MOEPP_K_GEMM2 = 5,   /* grouped GEMM W2                                   */
@@ -272,7 +274,9 @@ moepp_status moepp_get_balance(moepp_ctx *ctx, const float **f, const float **P,
                                const float **loss);
 
 /*
- * Kernel-variant selection, for tests and tuning: 0 = automatic (default),
+ * Kernel-variant selection, for tests and tuning: 0 = automatic (default;
+ * calls with at most 256 tokens use a router that splits the reduction over
+ * D across workgroups, in plain fp32 FMA, for either activation type),
  * 1 = force the generic kernels (any supported shape, plain fp32 FMA),
  * 2 = require the MFMA kernels (EUNSUPPORTED at call time if the shape or
  * type has none).

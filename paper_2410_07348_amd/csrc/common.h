@@ -15,6 +15,10 @@ constexpr int kMaxTopK = 8;       // K
 constexpr int kMaxConst = 8;      // constant experts
 constexpr int kWave = 64;         // CDNA wavefront
 
+// Calls with at most this many tokens take the router that splits the
+// reduction over D across workgroups.
+constexpr int kRouterSmallT = 256;
+
 // Permutation: one wave owns a chunk of kPermChunk consecutive slots.
 constexpr int kPermIters = 4;
 constexpr int kPermChunk = kWave * kPermIters;
@@ -83,6 +87,7 @@ struct Workspace {
     void *wsplit;        // router_split_bytes(D, N + 2 n_const)
     double *bal_partial; // [kBalWaves][kMaxExperts] partial sums of Softmax(G(x))
     float *bal;          // f [N], P [N], L_b [1]  (Eq.7)
+    float *router_partial; // router_small_bytes(): per-slice dot products of the few-token router
 };
 
 // Expert capacities (Eq.8), by value in the kernel arguments.  on = false: unlimited.
@@ -127,6 +132,9 @@ struct CombineArgs {
 // Launchers (each returns hipGetLastError() after its launches).
 // `bf16` selects the activation type; `which` selects GEMM1 / GEMM2.
 hipError_t launch_router_generic(const RouterArgs &a, bool bf16, hipStream_t s);
+// T <= kRouterSmallT only; partial: router_small_bytes() of scratch
+hipError_t launch_router_small(const RouterArgs &a, bool bf16, float *partial, hipStream_t s);
+size_t router_small_bytes();
 bool router_mfma_supported(const Dims &d);
 hipError_t launch_router_mfma(const RouterArgs &a, hipStream_t s);
 size_t router_split_bytes(int D, int rows);
@@ -134,6 +142,10 @@ size_t router_split_bytes(int D, int rows);
 hipError_t launch_perm_hist(const Dims &d, const Workspace &w, hipStream_t s);
 hipError_t launch_perm_scan(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s);
 hipError_t launch_perm_scatter(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s);
+// all three steps in one workgroup, for 0 < T*k <= kPermSmallSlots
+constexpr int kPermSmallWaves = 16;
+constexpr int kPermSmallSlots = kPermSmallWaves * kPermChunk;
+hipError_t launch_perm_small(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s);
 // f_i, P_i and L_b of Eq.7 from the logits of the routed call and the counts of the permutation
 hipError_t launch_balance(const Dims &d, const Workspace &w, const float *out_gate, float tau,
                           hipStream_t s);

@@ -7,17 +7,27 @@
 //   GEMM2: yffn[r,d] = W2_e[d,:] . h[r,:]
 // Both are C[m,n] = sum_k A[m,k] B[n,k] with A and B K-major, fp32 accumulation.
 //
-// Work decomposition: one workgroup per (M tile of one expert, N tile).  The
-// M tiles are enumerated on the device from the group offsets (no host sync):
-// expert e owns ceil(count_e / BM) tiles; surplus workgroups exit at once.
+// Work decomposition: output tiles of BM x BN (256 x 256 by default; M tiles
+// never cross an expert).  The tiles are enumerated on the device from the
+// group offsets (no host sync): expert e owns ceil(count_e / BM) M tiles; the
+// numbering walks patches of 8 x 4 tiles and deals the patches to the eight
+// XCDs round-robin, so that the tiles that run together on one XCD share their
+// A and B panels in that XCD's L2.  In the default (persistent) geometry one
+// workgroup per CU walks the tile list with stride gridDim; it looks up and
+// gathers the rows of its next tile while the current one computes and issues
+// that tile's first K stages before the epilogue of the current one.
 // A rows of GEMM1 are gathered straight from x through src_of (no permuted
-// copy of x is ever written).  A and B tiles of 64 K-elements are staged in
-// LDS (double buffered, 16-byte chunks XOR-swizzled by row so that the MFMA
-// operand reads do not pile on one bank group); each wave owns a TM x TN
-// sub-tile as 32x32 MFMA blocks.  The weight fragment is fed as the first MFMA
-// operand, so a lane ends up with four consecutive output columns of one row
-// and the epilogue can pack them into one 8-byte LDS write; the output tile is
-// then written to memory with 16-byte row-contiguous stores.
+// copy of x is ever written).  K tiles of 32 elements travel from memory
+// straight into a ring of LDS stages (global_load_lds, 16-byte chunks
+// XOR-swizzled by row so that the MFMA operand reads do not pile on one bank
+// group); a few dedicated loader waves issue them, one memory instruction after
+// each MFMA, and every wave owns a (BM/WM) x (BN/WN) sub-tile of MFMA blocks.
+// The weight fragment is fed as the first MFMA operand, so a lane ends up with
+// four consecutive output columns of one row and the epilogue can pack them
+// into one 8-byte LDS write; the output tile is then written to memory with
+// 16-byte row-contiguous stores.  The weights are read from a packed copy in
+// panels of 256 rows x K slabs (one K tile of a panel is contiguous); GEMM1
+// writes h in K-slab-major order so that GEMM2's A tiles are contiguous too.
 //
 // GEMM1 reads the packed [2F, D] matrix in which W1 and W3 rows alternate in
 // blocks of 32: 32x32 blocks with even index hold silu's argument, the next

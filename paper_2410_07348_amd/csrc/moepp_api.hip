@@ -81,6 +81,7 @@ size_t layout(const moepp_desc *d, char *base, Workspace *ws) {
     w.wsplit = take(d->act == MOEPP_BF16 ? router_split_bytes(d->D, (int)N + 2 * d->n_const) : 0);
     w.bal_partial = (double *)take((size_t)kBalWaves * kMaxExperts * sizeof(double));
     w.bal = (float *)take((2 * N + 1) * 4);
+    w.router_partial = (float *)take(router_small_bytes());
     if (ws) *ws = w;
     return off;
 }
@@ -181,8 +182,10 @@ moepp_status do_route(moepp_ctx *c, hipStream_t s, int T, const void *x, const f
     c->last_out_gate = out_gate;
     if (T == 0) return MOEPP_OK;
     KernelTimer kt(c, s, MOEPP_K_ROUTER);
-    hipError_t e = mfma ? launch_router_mfma(a, s)
-                        : launch_router_generic(a, c->desc.act == MOEPP_BF16, s);
+    const bool bf16 = c->desc.act == MOEPP_BF16;
+    hipError_t e;
+    if (c->variant == 0 && T <= kRouterSmallT) e = launch_router_small(a, bf16, c->ws.router_partial, s);
+    else e = mfma ? launch_router_mfma(a, s) : launch_router_generic(a, bf16, s);
     return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
 }
 
@@ -191,6 +194,18 @@ moepp_status do_permute(moepp_ctx *c, hipStream_t s, int T, int k) {
     c->last_T = T;
     c->last_k = k;
     hipError_t e;
+    if (T > 0 && T * k <= kPermSmallSlots) {
+        {
+            KernelTimer kt(c, s, MOEPP_K_SCATTER);
+            e = launch_perm_small(d, c->ws, c->cap, s);
+        }
+        if (e != hipSuccess) return MOEPP_EHIP;
+        if (c->bal_tau > 0.0) {
+            KernelTimer kt(c, s, MOEPP_K_BALANCE);
+            e = launch_balance(d, c->ws, c->last_out_gate, (float)c->bal_tau, s);
+        }
+        return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
+    }
     {
         KernelTimer kt(c, s, MOEPP_K_HIST);
         e = launch_perm_hist(d, c->ws, s);

@@ -109,6 +109,7 @@ def test_fp32_layers_all_tokens(kw):
     (dict(T=777, D=256, F=128, n_ffn=4, n_zero=2, n_copy=2, n_const=4, k=4, seed=102), 0.5, 0.25),
     (dict(T=600, D=128, F=128, n_ffn=8, n_zero=0, n_copy=0, n_const=0, seed=103), 0.8, 1.0),
     (dict(T=300, D=256, F=256, bias="normal", seed=104), 1.0, 0.1),
+    (dict(T=2500, D=128, F=128, n_ffn=6, seed=105), 0.9, 0.5),     # three-kernel permutation
 ])
 def test_expert_capacity_and_balance_statistics(kw, gamma, tau, variant):
     s = small_shape("cap", **kw)
@@ -211,6 +212,29 @@ def test_tiny_token_counts(kw):
         check_layer(s, inp, res)
 
 
+@pytest.mark.parametrize("act", ["bf16", "f32"])
+@pytest.mark.parametrize("kw", [
+    dict(T=256, seed=111),                       # last size of the few-token router
+    dict(T=257, seed=112),                       # first size of the ordinary routers
+    dict(T=2048, seed=113),                      # 4096 slots: last size of the one-workgroup permutation
+    dict(T=2049, seed=114),                      # first size of the three-kernel permutation
+    dict(T=1366, k=3, seed=115),                 # 4098 slots
+    dict(T=200, D=1000, F=64, n_ffn=3, seed=116),  # D not a multiple of the router's K tile
+    dict(T=100, D=4160, F=64, n_ffn=3, seed=117),  # more K tiles than slices, ragged last slice
+])
+def test_few_token_kernels_and_their_size_limits(kw, act):
+    """Calls on both sides of the sizes at which the library changes kernels,
+    with expert capacities and load-balance statistics on."""
+    s = small_shape("limits", act=act, **kw)
+    inp = make_inputs(s)
+    say("size limits", kw, act)
+    L = make_layer(s)
+    cap = L.capacity(s.T, 1.1, 0.75)
+    res = gpu_forward(s, inp, layer=L, cap=cap, balance_tau=0.75)
+    errs = check_layer(s, inp, res, cap=np.array(cap, np.int32), balance_tau=0.75)
+    say("  ", errs)
+
+
 def test_zero_tokens_and_smaller_T_than_T_max():
     s = small_shape("tmax", T=200)
     inp = make_inputs(s)
@@ -255,7 +279,7 @@ def test_two_runs_are_bytewise_identical():
 
 def test_step_calls_equal_the_fused_call_and_timing_reports():
     import torch
-    s = small_shape("steps", T=640, D=256, F=256)
+    s = small_shape("steps", T=2304, D=256, F=256)        # enough slots for the three-kernel permutation
     inp = make_inputs(s)
     dev = to_device(s, inp)
     L = make_layer(s)
