@@ -182,6 +182,13 @@ def roofline_numbers(shape, g):
         out["gemm1_tflops"] = fl1 / (km["gemm1"] * 1e-3) / 1e12
         out["gemm2_tflops"] = fl2 / (km["gemm2"] * 1e-3) / 1e12
         out["ffn_tflops"] = (fl1 + fl2) / ((km["gemm1"] + km["gemm2"]) * 1e-3) / 1e12
+        # algorithmic bytes of GEMM1: W1 and W3 of the experts that received rows, the
+        # gathered rows of x, h; below the ridge point the weight stream bounds the kernel
+        touched = sum(1 for c in g["counts"][:shape.n_ffn] if c > 0)
+        by1 = touched * 2 * F * D * b + R * D * b + R * F * b
+        out["gemm1_bytes"] = by1
+        out["gemm1_gbs"] = by1 / (km["gemm1"] * 1e-3) / 1e9
+        out["gemm1_flop_per_byte"] = fl1 / by1
     router_bytes = T * (D * b + (N * 4 if shape.residual else 0) + N * 4 + K * 8 + shape.n_const * 4)
     out["router_gbs"] = router_bytes / (km["router"] * 1e-3) / 1e9
     combine_bytes = (R + 2 * T) * D * b
@@ -286,7 +293,15 @@ def main():
         "permute_us": rf["permute_us"],
         "gemm2_tflops": rf.get("gemm2_tflops"),
     }
-    if "gemm1_tflops" in rf:
+    ridge = PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)     # flop per byte
+    if "gemm1_tflops" in rf and rf["gemm1_flop_per_byte"] < ridge:
+        # few rows per expert (decoding): GEMM1 streams the expert weights
+        result["roofline"] = {"kernel": "k_grouped_gemm<SwiGLU> (GEMM1: W1/W3 + SwiGLU)",
+                              "bound": "hbm", "achieved": rf["gemm1_gbs"], "peak": PEAK_HBM_GBS,
+                              "unit": "GB/s", "frac": rf["gemm1_gbs"] / PEAK_HBM_GBS,
+                              "traffic": traffic.get("gemm1"),
+                              "flop_per_byte": rf["gemm1_flop_per_byte"], "ridge_flop_per_byte": ridge}
+    elif "gemm1_tflops" in rf:
         result["roofline"] = {"kernel": "k_grouped_gemm<SwiGLU> (GEMM1: W1/W3 + SwiGLU)",
                               "bound": "mfma", "achieved": rf["gemm1_tflops"],
                               "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",

@@ -38,7 +38,9 @@ def oracle_chain(shape, layers, forced=None):
     return outs
 
 
-@pytest.mark.parametrize("kw", [dict(T=300, D=256, F=384, n_ffn=5), dict(T=1024, D=512, F=512, n_ffn=8)])
+@pytest.mark.parametrize("kw", [dict(T=300, D=256, F=384, n_ffn=5), dict(T=1024, D=512, F=512, n_ffn=8),
+                                dict(T=64, D=512, F=256, n_ffn=4),        # few-token router and permutation
+                                dict(T=2500, D=256, F=256, n_ffn=6)])    # three-kernel permutation
 def test_chain_of_layers_eager_and_as_one_graph(kw):
     import torch
     base = dict(T=300, D=256, F=384, n_ffn=5, n_zero=1, n_copy=1, n_const=2, k=2, act="bf16", seed=500)
