@@ -15,7 +15,11 @@
 // A and B panels in that XCD's L2.  In the default (persistent) geometry one
 // workgroup per CU walks the tile list with stride gridDim; it looks up and
 // gathers the rows of its next tile while the current one computes and issues
-// that tile's first K stages before the epilogue of the current one.
+// that tile's first K stages before the epilogue of the current one.  When
+// the whole problem is only a few rounds of tiles, a last round that fills at
+// most half of the workgroups is left to a second launch of the same kernel
+// with tiles of half the height (twice as many workgroups busy for about half
+// as long).
 // A rows of GEMM1 are gathered straight from x through src_of (no permuted
 // copy of x is ever written).  K tiles of 32 elements travel from memory
 // straight into a ring of LDS stages (global_load_lds, 16-byte chunks
@@ -55,6 +59,8 @@ struct GemmArgs {
     int n_ffn, topk;
     int n_ntiles;
     int jstride;             // persistent kernel: workgroups per XCD
+    int cut_grid;            // > 0: the tiles of a last, at most half-filled round of cut_grid
+                             // workgroups are left to the tail kernel (halves of 128 rows)
 };
 
 // silu(z) = z / (1 + e^-z) with the hardware exp2 and reciprocal (1 ulp each:
@@ -129,8 +135,11 @@ __device__ inline void wait_and_barrier() {
     asm volatile("" ::: "memory");
 }
 
-template <class G, bool SWIGLU>
+// TAIL: this launch computes what the main launch (tiles of 2 BM rows) left
+// over, as half tiles of BM rows; the tiles are numbered as in the main launch.
+template <class G, bool SWIGLU, bool TAIL = false>
 __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
+    constexpr int EBM = TAIL ? 2 * G::BM : G::BM;      // tile height of the numbering
     constexpr int BM = G::BM, BN = G::BN, WN = G::WN, NT = G::NT, NL = G::NL, RB = G::RB, CPR = G::CPR;
     constexpr int TM = G::TM, TN = G::TN, MB = G::MB, NB = G::NB, CA = G::CA, CB = G::CB;
     constexpr int STAGE = G::STAGE, NS = G::NS, BK = G::BK, KS = G::KS;
@@ -177,7 +186,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     const int gq = lane < a.n_ffn ? lane : a.n_ffn;
     const int o_lo = a.offsets[gq];
     const int o_hi = a.offsets[gq < a.n_ffn ? gq + 1 : gq];
-    const int mt_q = (o_hi - o_lo + BM - 1) / BM;              // 0 for lanes past the last group
+    const int mt_q = (o_hi - o_lo + EBM - 1) / EBM;            // 0 for lanes past the last group
     int incl = mt_q * Nt;                                       // inclusive prefix sum over lanes
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
@@ -185,13 +194,28 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         if (lane >= d) incl += up;
     }
     const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+    // A last round that fills at most half of the workgroups costs a whole
+    // tile time with most of the chip idle: those tiles [cut, total) go to the
+    // tail launch, which runs them as twice as many half tiles.
+    int cut = total;
+    if (a.cut_grid > 0) {
+        const int n_left = total % a.cut_grid;
+        if (n_left > 0 && 2 * n_left <= a.cut_grid) cut = total - n_left;
+    }
 
     int e = 0, row0 = 0, row_end = 0, nt = 0;                  // the tile being computed
     // tile j of this XCD -> (expert, first row, end of the group, n-tile); false past the end
     auto locate = [&](int j, int &t_e, int &t_row0, int &t_row_end, int &t_nt) -> bool {
         // XCD x takes patch-sized chunks x, x+8, x+16, ... of the order
         int L = ((j / (GM * GN)) * NXCD + blockIdx.x % NXCD) * (GM * GN) + j % (GM * GN);
-        if (L >= total) return false;
+        int half = 0;
+        if constexpr (TAIL) {
+            half = L & 1;
+            L = cut + (L >> 1);
+            if (L >= total) return false;
+        } else {
+            if (L >= cut) return false;
+        }
         const unsigned long long past = __ballot(incl > L);     // lanes whose groups end after tile L
         t_e = __builtin_ctzll(past);                            // L < total, so some lane has incl > L
         // (t_e is the same in every lane: these are scalar reads of lane t_e)
@@ -211,7 +235,9 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         L -= ng * gm * GN;
         const int mt = g * GM + L % gm;
         t_nt = ng * GN + L / gm;
-        t_row0 = b + mt * BM;
+        // (the second half of a group's last tile may lie past the group's rows: it
+        // is computed like any other and stores nothing)
+        t_row0 = b + mt * EBM + half * BM;
         return true;
     };
 
@@ -485,7 +511,9 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         constexpr int NB16 = TN / 16, MBH = TM / 32;          // B blocks; A blocks per phase
         constexpr int SLOTS = NB16 * MBH;                      // MFMAs per phase
         constexpr int L0 = LPT - LPT / 2, L1 = LPT / 2;        // tile loads issued in phase 0 / phase 1
-        static_assert(MBH + L0 <= SLOTS && NB16 + MBH + L1 <= SLOTS, "one memory operation per MFMA");
+        // (at most one memory operation per MFMA in the default geometry; smaller
+        // wave tiles put two after some of them)
+        static_assert(MBH + L0 <= 2 * SLOTS && NB16 + MBH + L1 <= 2 * SLOTS, "memory operations per MFMA");
         bf16x8 fa[2][MBH], fb[2][NB16];
         auto read_a = [&](const char *__restrict__ st, int blk) {
             return *reinterpret_cast<const bf16x8 *>(st + a_base + blk * 16 * RB + rd16);
@@ -752,7 +780,9 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
 
 bool ffn_mfma_supported(const Dims &d) { return d.D % 64 == 0 && d.F % 64 == 0; }
 
-template <class G>
+// TAILG: geometry (half the tile height of G) of a second launch that takes
+// over a sparsely filled last round of G's tiles; void: none.
+template <class G, class TAILG = void>
 static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
     GemmArgs a;
     a.offsets = f.offsets;
@@ -801,10 +831,30 @@ static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
         a.jstride = (int)(blocks / 8);
     }
     dim3 grid((unsigned)blocks), block(G::NT);
+    a.cut_grid = 0;
+    bool tail = false;
+    if constexpr (!std::is_void<TAILG>::value) {
+        static_assert(G::PERSIST && TAILG::PERSIST && 2 * TAILG::BM == G::BM && TAILG::BN == G::BN &&
+                          TAILG::BK == G::BK && TAILG::NS == G::NS,
+                      "the tail launch halves the tiles of the main launch");
+        // With many rounds a sparsely filled last one costs little (measured:
+        // nothing at 14 rounds and more, where the few busy CUs also clock
+        // higher); with few it is worth a second launch (+6 to +12 % at 3 - 5 rounds).
+        tail = max_mtiles * a.n_ntiles < 8 * blocks;
+        if (tail) a.cut_grid = (int)blocks;
+    }
     if (which == 0)
         hipLaunchKernelGGL((k_grouped_gemm<G, true>), grid, block, 0, s, a);
     else
         hipLaunchKernelGGL((k_grouped_gemm<G, false>), grid, block, 0, s, a);
+    if constexpr (!std::is_void<TAILG>::value) if (tail) {
+        // same grid and numbering; a workgroup finds at most one half tile, none
+        // when the main launch kept its last round
+        if (which == 0)
+            hipLaunchKernelGGL((k_grouped_gemm<TAILG, true, true>), grid, dim3(TAILG::NT), 0, s, a);
+        else
+            hipLaunchKernelGGL((k_grouped_gemm<TAILG, false, true>), grid, dim3(TAILG::NT), 0, s, a);
+    }
     return hipGetLastError();
 }
 
@@ -816,7 +866,9 @@ hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
     // reductions use two 64-deep stages.
     // MOEPP_GEMM_CFG selects other geometries, for tuning: 1 = 4 waves with
     // 128x128 wave tiles, 2 = ring of 3, 3 = two 64-deep stages, 5 = every
-    // wave loads, 6 = 32x32x16 MFMA blocks, 7 = 128-row tiles.
+    // wave loads, 6 = 32x32x16 MFMA blocks, 7 = 128-row tiles (4 waves,
+    // 32x32x16), 8 = 128-row tiles in the default wave layout, 9 = the default
+    // without the tail launch.
     const char *v = getenv("MOEPP_GEMM_CFG");
     int cfg = v ? atoi(v) : 0;
     const int K = which == 0 ? f.d.D : f.d.F;
@@ -832,7 +884,11 @@ hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
         case 5: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);
         case 7: return launch_cfg<Geo<128, 256, 1, 4, 32, 5, 0, true>>(f, which, s);
         case 6: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true>>(f, which, s);
-        default: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true, 16>>(f, which, s);
+        case 8: return launch_cfg<Geo<128, 256, 2, 4, 32, 5, 4, true, 16>>(f, which, s);
+        case 9: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true, 16>>(f, which, s);
+        default:
+            return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true, 16>, Geo<128, 256, 2, 4, 32, 5, 4, true, 16>>(
+                f, which, s);
     }
 }
 
