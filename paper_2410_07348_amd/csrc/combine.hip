@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kCombineWaves *kWave) void k_combine(CombineArgs a)
         for (int s = 0; s < kMaxTopK; ++s) {
             if (s < K) {
                 if (p_row[s]) {
-                    ActVec<AT> rv = load_vec(p_row[s] + d);
+                    ActVec<AT> rv = load_vec_stream(p_row[s] + d);   // read once
 #pragma unroll
                     for (int i = 0; i < V; ++i) acc[i] = fmaf(g_row[s], rv.get(i), acc[i]);
                 } else if (p_v[s]) {
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kCombineWaves *kWave) void k_combine(CombineArgs a)
         ActVec<AT> ov;
 #pragma unroll
         for (int i = 0; i < V; ++i) ov.set(i, acc[i]);
-        store_vec(ot + d, ov);
+        store_vec_stream(ot + d, ov);
     }
 }
 
