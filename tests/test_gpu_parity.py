@@ -315,6 +315,25 @@ def test_mfma_and_generic_kernels_agree():
     assert rel_err(b["out"][same], a["out"][same]) <= 1e-2
 
 
+def test_gemm_tail_launch_is_bitwise_the_single_launch(monkeypatch):
+    """A problem of a few rounds of tiles whose last round is sparsely filled is
+    finished by a second launch with half-height tiles: same bits as one launch,
+    and right against the oracle."""
+    s = small_shape("tail", T=9000, D=512, F=1024, n_ffn=5, seed=131)
+    inp = make_inputs(s)
+    monkeypatch.setenv("MOEPP_GEMM_CFG", "9")        # the default geometry without the tail launch
+    a = gpu_forward(s, inp, variant=2)
+    monkeypatch.delenv("MOEPP_GEMM_CFG")
+    b = gpu_forward(s, inp, variant=2)
+    m_tiles = int(sum(-(-int(c) // 256) for c in b["counts"][:s.n_ffn]))
+    left1, left2 = m_tiles * (2 * s.F // 256) % 256, m_tiles * (s.D // 256) % 256
+    say("tail: m tiles", m_tiles, "leftover tiles GEMM1", left1, "GEMM2", left2)
+    assert 0 < left1 <= 128 and 0 < left2 <= 128     # both GEMMs take the tail path (256 workgroups)
+    for k in ("out", "yffn", "h", "topk_idx", "row_of"):
+        assert np.array_equal(a[k], b[k]), k
+    check_layer(s, inp, b)
+
+
 # ------------------------------------------------- the benchmark's own shapes
 def _full_size(name, n_sample, check_inter=True):
     s = WORKLOADS[name]
