@@ -251,7 +251,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the layer on one GPU only; --gpus %d is not "
-                 "supported (sharding is described in DESIGN.md)" % args.gpus)
+                 "supported (tokens are independent: shard T, or the FFN experts, across GPUs)" % args.gpus)
 
     import torch
     from workloads import WORKLOADS, make_inputs, ffn_work_fraction
