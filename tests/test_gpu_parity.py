@@ -354,13 +354,13 @@ def test_workload_small_all_tokens():
 
 
 def test_workload_mid_ragged_groups_sampled():
-    s, res, errs = _full_size("mid", 768)
+    s, res, errs = _full_size("mid", 4096)
     c = res["counts"][:s.n_ffn]
     assert c.max() > 8 * max(c.min(), 1)
 
 
 def test_workload_skew_sampled():
-    s, res, errs = _full_size("skew", 768)
+    s, res, errs = _full_size("skew", 4096)
     c = res["counts"].astype(np.float64)
     assert abs(c[s.n_ffn:].sum() / c.sum() - 0.5) < 0.03
     assert abs(c[0] / c[1:s.n_ffn].mean() - 4.0) < 0.5
@@ -371,5 +371,11 @@ def test_workload_smallbatch_all_tokens():
 
 
 def test_workload_large_sampled():
-    s, res, errs = _full_size("large", 384)
+    s, res, errs = _full_size("large", 4096)
     assert abs(errs["R"] / (s.T * s.k) - s.n_ffn / s.N) < 0.01
+
+
+def test_workload_large_vanilla_sampled():
+    """The vanilla comparison layer of the benchmark (20 FFN experts, none other)."""
+    s, res, errs = _full_size("large_vanilla20", 1024, check_inter=False)
+    assert errs["R"] == s.T * s.k
