@@ -375,6 +375,25 @@ def test_workload_large_sampled():
     assert abs(errs["R"] / (s.T * s.k) - s.n_ffn / s.N) < 0.01
 
 
+def test_workload_large_two_kernel_families_all_tokens():
+    """Every token of the benchmark workload through both kernel families (plain
+    fp32 FMA kernels and the MFMA kernels): same routing except inside float32
+    noise, outputs within the bf16 tolerance.  Extends the sampled oracle check
+    above to all 32768 tokens."""
+    s = WORKLOADS["large"]
+    inp = make_inputs(s)
+    L = make_layer(s)
+    dev = to_device(s, inp)
+    a = gpu_forward(s, inp, variant=1, layer=L, dev=dev, intermediates=False)
+    b = gpu_forward(s, inp, variant=2, layer=L, dev=dev, intermediates=False)
+    assert rel_err(b["out_gate"], a["out_gate"]) <= 1e-5
+    same = (a["topk_idx"] == b["topk_idx"]).all(axis=1)
+    say("large, both families: tokens routed alike", int(same.sum()), "of", s.T)
+    assert same.mean() > 0.999
+    assert rel_err(b["out"][same], a["out"][same]) <= 1e-2
+    assert rel_err(b["topk_w"][same], a["topk_w"][same]) <= 1e-5
+
+
 def test_workload_large_vanilla_sampled():
     """The vanilla comparison layer of the benchmark (20 FFN experts, none other)."""
     s, res, errs = _full_size("large_vanilla20", 1024, check_inter=False)
