@@ -81,6 +81,7 @@ template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int LW_ = 0, boo
           int MI_ = 32>
 struct Geo {
     static constexpr int MI = MI_;
+    static constexpr bool PAIR = MI_ == 16;            // GEMM1 issues the A loads of two K tiles together
     static_assert(MI_ == 32 || (MI_ == 16 && BK_ == 32 && NS_ >= 3), "16x16x32 blocks: one MFMA K step per 32-deep stage, ring path");
     static constexpr bool PERSIST = PERSIST_;          // one workgroup per CU runs tile after tile
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
@@ -511,9 +512,21 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         constexpr int NB16 = TN / 16, MBH = TM / 32;          // B blocks; A blocks per phase
         constexpr int SLOTS = NB16 * MBH;                      // MFMAs per phase
         constexpr int L0 = LPT - LPT / 2, L1 = LPT / 2;        // tile loads issued in phase 0 / phase 1
+        // PAIR (GEMM1): the A rows are 64-byte pieces of gathered rows of x, the
+        // two halves of a 128-byte line belong to consecutive K tiles.  Fetched a
+        // whole tile time apart, the line travels from L2 twice (40 B/clk/CU in a
+        // microbenchmark of the load path); fetched by consecutive loads, once
+        // (55 B/clk/CU).  So the loads of a pair of tiles (T, T+1), T even, go
+        // out in this order: during the tile that refills T's stage the CB loads
+        // of B(T), during the next one A(T)[0], A(T+1)[0], A(T)[1], A(T+1)[1], ...
+        // and then B(T+1).  (A(T) leaves one tile time later than otherwise.)
+        constexpr bool PAIR = SWIGLU && G::PAIR;
+        constexpr int PL0 = CB - CB / 2, PL1 = CB / 2;                       // even tile: B only
+        constexpr int QL0 = (2 * CA + CB) - (2 * CA + CB) / 2, QL1 = (2 * CA + CB) / 2;   // odd tile
         // (at most one memory operation per MFMA in the default geometry; smaller
         // wave tiles put two after some of them)
         static_assert(MBH + L0 <= 2 * SLOTS && NB16 + MBH + L1 <= 2 * SLOTS, "memory operations per MFMA");
+        static_assert(!PAIR || (MBH + QL0 <= 2 * SLOTS && NB16 + MBH + QL1 <= 2 * SLOTS), "memory operations per MFMA");
         bf16x8 fa[2][MBH], fb[2][NB16];
         auto read_a = [&](const char *__restrict__ st, int blk) {
             return *reinterpret_cast<const bf16x8 *>(st + a_base + blk * 16 * RB + rd16);
@@ -522,11 +535,26 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
             return *reinterpret_cast<const bf16x8 *>(st + b_base + blk * 16 * RB + rd16);
         };
         // one phase: SLOTS MFMAs, after each at most one read or tile load
-        auto phase = [&](auto ph_c, auto par_c, auto read_c, auto n_load_c, const char *__restrict__ st,
-                         int kt_issue, char *__restrict__ wr) {
+        // load n of the loads a tile of parity P issues (for tile kt_issue into
+        // stage wr; PAIR, odd tile: also for tile kt_issue - 1 into stage wr_prev)
+        auto issue_op = [&](auto par_c, int n, int kt_issue, char *__restrict__ wr, char *__restrict__ wr_prev) {
+            constexpr int P = decltype(par_c)::value;
+            if constexpr (!PAIR) {
+                issue_one(n, kt_issue, wr);
+            } else if constexpr (P == 0) {
+                issue_one(CA + n, kt_issue, wr);
+            } else {
+                if (n >= 2 * CA) issue_one(n - CA, kt_issue, wr);
+                else if (n % 2 == 0) issue_one(n / 2, kt_issue - 1, wr_prev);
+                else issue_one(n / 2, kt_issue, wr);
+            }
+        };
+        auto phase = [&](auto ph_c, auto par_c, auto read_c, auto n_load_c, auto load_base_c,
+                         const char *__restrict__ st, int kt_issue, char *__restrict__ wr,
+                         char *__restrict__ wr_prev) {
             constexpr int PH = decltype(ph_c)::value, P = decltype(par_c)::value;
             constexpr bool READ = decltype(read_c)::value;
-            constexpr int N_LOAD = decltype(n_load_c)::value;
+            constexpr int N_LOAD = decltype(n_load_c)::value, LOAD_BASE = decltype(load_base_c)::value;
             constexpr int N_READ = PH == 0 ? MBH : NB16 + MBH;
             constexpr int OPS = N_READ + N_LOAD;
 #pragma unroll
@@ -540,7 +568,7 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
                     for (int o = 0; o < OPS; ++o) {
                         if (o * SLOTS / OPS != idx) continue;
                         if (o >= N_READ) {
-                            issue_one((PH == 0 ? 0 : L0) + o - N_READ, kt_issue, wr);
+                            issue_op(par_c, LOAD_BASE + o - N_READ, kt_issue, wr, wr_prev);
                         } else if (READ) {
                             if (PH == 0) fa[1][o] = read_a(st, MBH + o);          // this tile, phase 1
                             else if (o < NB16) fb[1 - P][o] = read_b(st, o);       // next tile
@@ -554,22 +582,29 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         typedef std::false_type no_t;
         // One tile.  cur / nxt / wr are three different stages (restrict).
         auto k_tile = [&](auto par_c, const char *__restrict__ cur, const char *__restrict__ nxt,
-                          char *__restrict__ wr, int kt_issue, auto vm_c, auto issue_c, auto last_c) {
-            constexpr int VM = decltype(vm_c)::value;
+                          char *__restrict__ wr, char *__restrict__ wr_prev, int kt_issue, auto vm_c,
+                          auto issue_c, auto last_c) {
+            constexpr int VM = decltype(vm_c)::value, P = decltype(par_c)::value;
             constexpr bool ISSUE = decltype(issue_c)::value, LAST = decltype(last_c)::value;
-            typedef std::integral_constant<int, ISSUE && LOADER ? L0 : 0> l0_t;
-            typedef std::integral_constant<int, ISSUE && LOADER ? L1 : 0> l1_t;
+            constexpr int N0 = !(ISSUE && LOADER) ? 0 : !PAIR ? L0 : P == 0 ? PL0 : QL0;
+            constexpr int N1 = !(ISSUE && LOADER) ? 0 : !PAIR ? L1 : P == 0 ? PL1 : QL1;
+            typedef std::integral_constant<int, N0> l0_t;
+            typedef std::integral_constant<int, N1> l1_t;
+            typedef std::integral_constant<int, 0> base0_t;
             __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): operands read during the previous phase
             __builtin_amdgcn_sched_barrier(0);
-            phase(std::integral_constant<int, 0>{}, par_c, yes_t{}, l0_t{}, cur, kt_issue, wr);
+            phase(std::integral_constant<int, 0>{}, par_c, yes_t{}, l0_t{}, base0_t{}, cur, kt_issue, wr, wr_prev);
             if constexpr (!LAST) wait_and_barrier<VM>();   // tile kt+1 landed; my reads of tile kt complete
             else __builtin_amdgcn_s_waitcnt(0xC07F);
             __builtin_amdgcn_sched_barrier(0);
-            phase(std::integral_constant<int, 1>{}, par_c, std::integral_constant<bool, !LAST>{}, l1_t{},
-                  nxt, kt_issue, wr);
+            phase(std::integral_constant<int, 1>{}, par_c, std::integral_constant<bool, !LAST>{}, l1_t{}, l0_t{},
+                  nxt, kt_issue, wr, wr_prev);
         };
-        int s_cur = S0, s_nxt = (S0 + 1) % NS, s_wr = (S0 + NS - 1) % NS;
+        // s_wr: the stage the tile being computed refills (tile kt + NS - 1);
+        // s_prev: the stage the tile before it refilled
+        int s_cur = S0, s_nxt = (S0 + 1) % NS, s_wr = (S0 + NS - 1) % NS, s_prev = (S0 + NS - 2) % NS;
         auto rotate = [&]() {
+            s_prev = s_wr;
             s_wr = s_cur;
             s_cur = s_nxt;
             s_nxt = s_nxt + 1 == NS ? 0 : s_nxt + 1;
@@ -579,25 +614,37 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
         for (int j = 0; j < NB16; ++j) fb[0][j] = read_b(lds + S0 * STAGE, j);
 #pragma unroll
         for (int i = 0; i < MBH; ++i) fa[0][i] = read_a(lds + S0 * STAGE, i);
-        typedef std::integral_constant<int, (NS - 3) * LPT + L0> vm_steady_t;
+        // Loads that may still be in flight at a tile's barrier, when the next
+        // tile must have landed (loads complete in the order of issue).  In
+        // tile order: the tiles after the next one, and this tile's phase 0.
+        // PAIR, at even tile T (tile T+1 went out last during tile T-3): the loads
+        // of tiles T-2 and T-1 and of this phase 0; at odd tile T+1 (the last load
+        // of tile T+2 is A(T+2)[CA-1], issued during T-1 and followed there by
+        // A(T+3)[CA-1] and B(T+3)): those 1 + CB, tile T's and this phase 0.  The
+        // first tiles of an output tile were issued in tile order, which leaves
+        // at least as many younger loads at each of these points.
+        constexpr int VM0 = !PAIR ? (NS - 3) * LPT + L0 : CB + (2 * CA + CB) + PL0;
+        constexpr int VM1 = !PAIR ? (NS - 3) * LPT + L0 : (1 + CB) + CB + QL0;
+        static_assert(NS == 5 && VM0 < 64 && VM1 < 64, "ring of five stages; vmcnt has six bits");
         typedef std::integral_constant<int, 0> par0_t;
         typedef std::integral_constant<int, 1> par1_t;
         // KT is even and NS - 1 = 4 tiles are peeled: the steady tiles come in pairs
-        static_assert(NS == 5, "pairing of the tiles assumes an even number of peeled tiles");
         for (int kt = 0; kt < KT - (NS - 1); kt += 2) {
-            k_tile(par0_t{}, lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, kt + NS - 1,
-                   vm_steady_t{}, yes_t{}, no_t{});
+            k_tile(par0_t{}, lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, lds + s_prev * STAGE,
+                   kt + NS - 1, std::integral_constant<int, VM0>{}, yes_t{}, no_t{});
             rotate();
-            k_tile(par1_t{}, lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, kt + NS,
-                   vm_steady_t{}, yes_t{}, no_t{});
+            k_tile(par1_t{}, lds + s_cur * STAGE, lds + s_nxt * STAGE, lds + s_wr * STAGE, lds + s_prev * STAGE,
+                   kt + NS, std::integral_constant<int, VM1>{}, yes_t{}, no_t{});
             rotate();
         }
         // the last NS-1 tiles: nothing left to issue, fewer loads in flight
+        // (PAIR: tiles KT-2 and KT-1 went out as A, A, ..., B during tile KT-5)
         auto tail = [&](auto t_c) {
             constexpr int t = decltype(t_c)::value;
             constexpr int younger = NS - 3 - t > 0 ? NS - 3 - t : 0;
+            constexpr int VMT = !PAIR ? younger * LPT : t == 0 ? CB + (2 * CA + CB) : t == 1 ? 1 + CB : 0;
             k_tile(std::integral_constant<int, t % 2>{}, lds + s_cur * STAGE, lds + s_nxt * STAGE,
-                   lds + s_wr * STAGE, 0, std::integral_constant<int, younger * LPT>{}, no_t{},
+                   lds + s_wr * STAGE, lds + s_prev * STAGE, 0, std::integral_constant<int, VMT>{}, no_t{},
                    std::integral_constant<bool, t == NS - 2>{});
             rotate();
         };
