@@ -884,10 +884,11 @@ static hipError_t launch_cfg(const FfnArgs &f, int which, hipStream_t s) {
         static_assert(G::PERSIST && TAILG::PERSIST && 2 * TAILG::BM == G::BM && TAILG::BN == G::BN &&
                           TAILG::BK == G::BK && TAILG::NS == G::NS,
                       "the tail launch halves the tiles of the main launch");
-        // With many rounds a sparsely filled last one costs little (measured:
-        // nothing at 14 rounds and more, where the few busy CUs also clock
-        // higher); with few it is worth a second launch (+6 to +12 % at 3 - 5 rounds).
-        tail = max_mtiles * a.n_ntiles < 8 * blocks;
+        // With few rounds a sparsely filled last one is worth a second launch
+        // (measured: +6 to +12 % at 3 - 5 rounds, +2 % at 13); with many it
+        // costs little, the few busy CUs also clock higher (nothing at 36).
+        // The host knows an upper bound of the number of rounds only.
+        tail = max_mtiles * a.n_ntiles < 24 * blocks;
         if (tail) a.cut_grid = (int)blocks;
     }
     if (which == 0)
