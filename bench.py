@@ -25,7 +25,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 import numpy as np
 
@@ -41,7 +40,7 @@ def run_gpu(shape, inp, steps, warmup, capacity=None):
     """Timed steps of moepp_layer_forward on cuda:0.  Returns a dict.
     capacity = (gamma, tau): expert capacities of Eq.8 and the statistics of Eq.7 on."""
     import torch
-    from helpers import make_layer, to_device
+    from paper_2410_07348_amd.torch_util import make_layer, to_device
     dev = to_device(shape, inp)
     L = make_layer(shape)
     packed = L.pack_experts(dev["w1"], dev["w3"], dev["w2"]) if shape.n_ffn else None
@@ -91,7 +90,7 @@ def run_chain(shape, inp, n_layers, steps, warmup):
     gating residual input of the next, Eq.6; the first has none), eagerly and as one
     HIP graph: what the launch overhead of the seven kernels per layer costs."""
     import torch
-    from helpers import make_layer, to_device
+    from paper_2410_07348_amd.torch_util import make_layer, to_device
     dev = to_device(shape, inp)
     L = make_layer(shape)
     packed = L.pack_experts(dev["w1"], dev["w3"], dev["w2"]) if shape.n_ffn else None

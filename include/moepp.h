@@ -235,11 +235,13 @@ moepp_status moepp_get_timing(moepp_ctx *ctx, float *ms);
  * Expert capacity (Sec. 3.3, Eq.8).  moepp_capacity is host arithmetic: it
  * writes into cap_host[N] (host array)
  *   C_i = ceil(gamma * tau * S / (tau N_FFN + N_ZC))   for an FFN expert,
- *   C_i = ceil(gamma * S / (tau N_FFN + N_ZC))         for a zero-computation expert,
- * with S = T * k, the number of (token, slot) assignments of a call (Eq.8's
- * "number of tokens" is read as the assignments: with T itself the capacities
- * would add up to gamma*T places for k*T assignments).  A value that exceeds
- * an integer by less than 1e-9 relative counts as that integer.
+ *   C_i = ceil(gamma * S / (tau N_FFN + N_ZC))         for a zero-computation expert.
+ * per_assignment != 0 (the reading this library's benchmark and tests use):
+ * S = T * k, the number of (token, slot) assignments of a call; with T itself
+ * the capacities add up to gamma*T places for k*T assignments.
+ * per_assignment == 0: S = T, the number of tokens, Eq.8 as it is printed
+ * (capacities k times smaller).  A value that exceeds an integer by less than
+ * 1e-9 relative counts as that integer.
  * EINVAL: null pointer, T or k outside the descriptor, gamma or tau not positive.
  *
  * moepp_set_capacity copies cap_host[N] into the context (NULL switches the
@@ -253,7 +255,7 @@ moepp_status moepp_get_timing(moepp_ctx *ctx, float *ms);
  * are the prefix sums of the kept FFN rows.  EINVAL: a negative capacity.
  */
 moepp_status moepp_capacity(const moepp_desc *desc, int32_t T, int32_t k, double gamma,
-                            double tau, int32_t *cap_host);
+                            double tau, int32_t per_assignment, int32_t *cap_host);
 moepp_status moepp_set_capacity(moepp_ctx *ctx, const int32_t *cap_host);
 moepp_status moepp_get_kept(moepp_ctx *ctx, const int32_t **kept);
 
@@ -279,7 +281,9 @@ moepp_status moepp_get_balance(moepp_ctx *ctx, const float **f, const float **P,
  * D across workgroups, in plain fp32 FMA, for either activation type),
  * 1 = force the generic kernels (any supported shape, plain fp32 FMA),
  * 2 = require the MFMA kernels (EUNSUPPORTED at call time if the shape or
- * type has none).
+ * type has none), 3 = as 2, and the grouped GEMM leaves a sparsely filled last
+ * round of tiles to its main launch instead of a second launch with tiles of
+ * half the height (same results bit for bit; lets a test compare the two).
  */
 moepp_status moepp_set_variant(moepp_ctx *ctx, int32_t variant);
 

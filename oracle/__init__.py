@@ -121,13 +121,15 @@ def permute(sh, topk_idx):
     return {"counts": counts, "offsets": offsets, "row_of": row_of, "src_of": src_of}
 
 
-def capacity(sh, gamma, tau):
-    """Expert capacities C_i of Eq.8 (int32 [N]) for T*K assignments."""
+def capacity(sh, gamma, tau, per_assignment=True):
+    """Expert capacities C_i of Eq.8 (int32 [N]): for T*K assignments, or with
+    per_assignment=False for T tokens, the equation as it is printed."""
     cs = _cshape(sh.T, sh.D, sh.F, sh.n_ffn, sh.n_zero, sh.n_copy, sh.n_const, sh.k)
     N = sh.n_ffn + sh.n_zero + sh.n_copy + sh.n_const
     cap = np.empty(N, np.int32)
     rc = lib().moepp_oracle_capacity(ctypes.byref(cs), ctypes.c_double(gamma),
-                                     ctypes.c_double(tau), _p(cap, np.int32))
+                                     ctypes.c_double(tau), ctypes.c_int32(1 if per_assignment else 0),
+                                     _p(cap, np.int32))
     if rc != 0:
         raise ValueError("moepp_oracle_capacity: gamma and tau must be positive")
     return cap

@@ -34,6 +34,7 @@
  *    read as the number of (token, slot) assignments T*K (with T itself the
  *    capacities of Eq.8 sum to gamma*T for K*T assignments, so that at
  *    K = 2, gamma = 1.1 almost half of all assignments would be dropped);
+ *    the literal form, T tokens, can be asked for as well;
  *    C_i is rounded up to an integer; an expert keeps the first C_i of the
  *    assignments it received in (token, slot) order and the others are
  *    dropped: a dropped assignment contributes nothing to y (the token
@@ -218,19 +219,20 @@ int moepp_oracle_permute(const oracle_shape *s, const int32_t *topk_idx,
 /*
  * Expert capacity, Eq.8: C_i = gamma * tau * S / (tau N_FFN + N_ZC) for an FFN
  * expert and gamma * S / (tau N_FFN + N_ZC) for a zero-computation expert,
- * rounded up (a relative 1e-9 above an integer counts as that integer), with
- * S = T*K assignments (see the readings in the header).
+ * rounded up (a relative 1e-9 above an integer counts as that integer).
+ * per_assignment != 0: S = T*K assignments (the reading in the header);
+ * per_assignment == 0: S = T, the number of tokens, Eq.8 as it is printed.
  *   cap [N] int32
  */
 int moepp_oracle_capacity(const oracle_shape *s, double gamma, double tau,
-                          int32_t *cap)
+                          int32_t per_assignment, int32_t *cap)
 {
     const int N = n_experts(s);
     const int n_zc = N - s->n_ffn;
     const double denom = tau * (double)s->n_ffn + (double)n_zc;
     if (!(gamma > 0.0) || !(tau > 0.0) || !(denom > 0.0))
         return -1;
-    const double S = (double)s->T * (double)s->k;
+    const double S = per_assignment ? (double)s->T * (double)s->k : (double)s->T;
     for (int i = 0; i < N; ++i) {
         const double c = i < s->n_ffn ? gamma * tau * S / denom : gamma * S / denom;
         /* round up, but take a value that exceeds an integer only by the
@@ -410,11 +412,11 @@ int moepp_oracle_experts(const oracle_shape *s, const float *x,
     const int zc0 = s->n_ffn + s->n_zero + s->n_copy;
     int bad = 0;
 
-#pragma omp parallel for schedule(static)
+#pragma omp parallel for schedule(static) reduction(| : bad)
     for (int u = 0; u < n_tok; ++u) {
         const int t = tok_list ? tok_list[u] : u;
         if (t < 0 || t >= s->T) {
-            bad = 1;
+            bad |= 1;
             continue;
         }
         double *xf = (double *)malloc(sizeof(double) * D);

@@ -83,7 +83,7 @@ def load_library(build_if_missing: bool = True):
     L.moepp_set_variant.argtypes = [vp, i32]
     L.moepp_mfma_ceiling.argtypes = [vp, vp, c_size_t, i32, POINTER(ctypes.c_double)]
     L.moepp_capacity.argtypes = [POINTER(Desc), i32, i32, ctypes.c_double, ctypes.c_double,
-                                 POINTER(c_int32)]
+                                 i32, POINTER(c_int32)]
     L.moepp_set_capacity.argtypes = [vp, POINTER(c_int32)]
     L.moepp_get_kept.argtypes = [vp, POINTER(vp)]
     L.moepp_set_balance.argtypes = [vp, ctypes.c_double]
@@ -106,8 +106,19 @@ def _check(status, what):
         raise MoeppError(status, what)
 
 
-def _ptr(t):
-    return None if t is None else c_void_p(t.data_ptr())
+def _ptr(t, dtype=None, device=None):
+    """Device address of a torch tensor (None -> NULL).  The library reads raw
+    memory: a tensor of another type, on another device or not contiguous would
+    be misread without any error, so those are refused here."""
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("expected a %s tensor, got %s" % (dtype, t.dtype))
+    if device is not None and t.device != device:
+        raise ValueError("tensor is on %s, the layer on %s" % (t.device, device))
+    return c_void_p(t.data_ptr())
 
 
 def mfma_ceiling(iters=20000, reps=3, device="cuda:0"):
@@ -169,6 +180,12 @@ class Layer:
             pass
 
     # -- helpers -----------------------------------------------------------
+    def _act(self, t):
+        return _ptr(t, self.act_dtype, self.device)
+
+    def _f32(self, t):
+        return _ptr(t, self.torch.float32, self.device)
+
     def _stream(self):
         return c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
 
@@ -183,6 +200,8 @@ class Layer:
         t = self.torch
         nbytes = self.L.moepp_packed_bytes(byref(self.desc))
         packed = t.empty(nbytes, dtype=t.uint8, device=self.device)
+        for w in (w1, w3, w2):
+            self._act(w)
         ex = _Experts(w1.data_ptr() if w1 is not None else None,
                       w3.data_ptr() if w3 is not None else None,
                       w2.data_ptr() if w2 is not None else None)
@@ -192,7 +211,7 @@ class Layer:
 
     def set_router_bias(self, bias):
         self._bias = bias          # keep the tensor alive: the library keeps the pointer
-        _check(self.L.moepp_set_router_bias(self.ctx, _ptr(bias)), "moepp_set_router_bias")
+        _check(self.L.moepp_set_router_bias(self.ctx, self._f32(bias)), "moepp_set_router_bias")
 
     def set_variant(self, v):
         _check(self.L.moepp_set_variant(self.ctx, v), "moepp_set_variant")
@@ -214,10 +233,12 @@ class Layer:
             out = t.empty((T, self.desc.D), dtype=self.act_dtype, device=self.device)
         if out_gate is None:
             out_gate = t.empty((T, self.desc.N), dtype=t.float32, device=self.device)
-        _check(self.L.moepp_layer_forward(self.ctx, self._stream(), T, _ptr(x), _ptr(prev_gate),
-                                          _ptr(W_g), _ptr(W_res), _ptr(experts),
-                                          _ptr(const_vecs), _ptr(W_c), k, _ptr(out),
-                                          _ptr(out_gate)), "moepp_layer_forward")
+        _check(self.L.moepp_layer_forward(self.ctx, self._stream(), T, self._act(x),
+                                          self._f32(prev_gate), self._f32(W_g), self._f32(W_res),
+                                          _ptr(experts, t.uint8, self.device),
+                                          self._act(const_vecs), self._f32(W_c), k,
+                                          self._act(out), self._f32(out_gate)),
+               "moepp_layer_forward")
         self.last_T, self.last_k = T, k
         return out, out_gate
 
@@ -227,9 +248,9 @@ class Layer:
         T = x.shape[0]
         if out_gate is None:
             out_gate = t.empty((T, self.desc.N), dtype=t.float32, device=self.device)
-        _check(self.L.moepp_route(self.ctx, self._stream(), T, _ptr(x), _ptr(prev_gate),
-                                  _ptr(W_g), _ptr(W_res), _ptr(W_c), k, _ptr(out_gate)),
-               "moepp_route")
+        _check(self.L.moepp_route(self.ctx, self._stream(), T, self._act(x),
+                                  self._f32(prev_gate), self._f32(W_g), self._f32(W_res),
+                                  self._f32(W_c), k, self._f32(out_gate)), "moepp_route")
         self.last_T, self.last_k = T, k
         return out_gate
 
@@ -241,16 +262,17 @@ class Layer:
 
     def expert_ffn(self, x, experts, k=None):
         k = self.last_k if k is None else k
-        _check(self.L.moepp_expert_ffn(self.ctx, self._stream(), x.shape[0], _ptr(x),
-                                       _ptr(experts), k), "moepp_expert_ffn")
+        _check(self.L.moepp_expert_ffn(self.ctx, self._stream(), x.shape[0], self._act(x),
+                                       _ptr(experts, self.torch.uint8, self.device), k),
+               "moepp_expert_ffn")
 
     def combine(self, x, const_vecs, k=None, out=None):
         t = self.torch
         k = self.last_k if k is None else k
         if out is None:
             out = t.empty((x.shape[0], self.desc.D), dtype=self.act_dtype, device=self.device)
-        _check(self.L.moepp_combine(self.ctx, self._stream(), x.shape[0], _ptr(x),
-                                    _ptr(const_vecs), k, _ptr(out)), "moepp_combine")
+        _check(self.L.moepp_combine(self.ctx, self._stream(), x.shape[0], self._act(x),
+                                    self._act(const_vecs), k, self._act(out)), "moepp_combine")
         return out
 
     def get_routing(self):
@@ -269,11 +291,12 @@ class Layer:
             "src_of": self._view(p[5].value, T * k, t.int32),
         }
 
-    def capacity(self, T, gamma, tau, k=None):
-        """Expert capacities C_i of Eq.8 for a call with T tokens: list of N ints."""
+    def capacity(self, T, gamma, tau, k=None, per_assignment=True):
+        """Expert capacities C_i of Eq.8 for a call with T tokens: list of N ints
+        (per_assignment=False: Eq.8 with T tokens literally instead of T*k assignments)."""
         cap = (c_int32 * self.desc.N)()
         _check(self.L.moepp_capacity(byref(self.desc), T, self.desc.k if k is None else k,
-                                     gamma, tau, cap), "moepp_capacity")
+                                     gamma, tau, 1 if per_assignment else 0, cap), "moepp_capacity")
         return [int(v) for v in cap]
 
     def set_capacity(self, cap):

@@ -119,6 +119,7 @@ struct FfnArgs {
     void *h;              // [h_rows, F] K-slab-major; rows < R are written
     void *yffn;           // [R,D] row-major
     int h_rows;           // T_max * k
+    bool no_tail;         // tests: leave a sparsely filled last round of tiles to the main launch
 };
 
 struct CombineArgs {

@@ -39,8 +39,6 @@
 // same lane, so SwiGLU is applied in registers.
 #include "common.h"
 
-#include <stdlib.h>
-
 #include <type_traits>
 
 namespace moepp {
@@ -912,32 +910,17 @@ hipError_t launch_ffn_mfma(const FfnArgs &f, int which, hipStream_t s) {
     // 16x16x32 MFMA blocks, persistent workgroups, 32-deep K stages in a ring
     // of 5 (the whole 160 KB of LDS), which needs at least 4 K tiles; shorter
     // reductions use two 64-deep stages.
-    // MOEPP_GEMM_CFG selects other geometries, for tuning: 1 = 4 waves with
-    // 128x128 wave tiles, 2 = ring of 3, 3 = two 64-deep stages, 5 = every
-    // wave loads, 6 = 32x32x16 MFMA blocks, 7 = 128-row tiles (4 waves,
-    // 32x32x16), 8 = 128-row tiles in the default wave layout, 9 = the default
-    // without the tail launch.
-    const char *v = getenv("MOEPP_GEMM_CFG");
-    int cfg = v ? atoi(v) : 0;
     const int K = which == 0 ? f.d.D : f.d.F;
+    if (K / 32 < 4)                       // too few K tiles to fill a ring of stages
+        return launch_cfg<Geo<256, 256, 2, 4, 64, 2>>(f, which, s);
     // Few rows per expert (decoding, small batches): the GEMMs only stream
     // the weights, so use 128-row tiles: half of the (mostly wasted)
     // matrix work of a 256-row tile per byte of weights, bound by HBM instead.
-    if (cfg == 0 && (long long)f.d.T * f.d.k <= 128ll * f.d.n_ffn) cfg = 7;
-    if (K / 32 < 4) cfg = 3;              // too few K tiles to fill a ring of stages
-    switch (cfg) {
-        case 1: return launch_cfg<Geo<256, 256, 2, 2, 32, 5>>(f, which, s);
-        case 2: return launch_cfg<Geo<256, 256, 2, 4, 32, 3>>(f, which, s);
-        case 3: return launch_cfg<Geo<256, 256, 2, 4, 64, 2>>(f, which, s);
-        case 5: return launch_cfg<Geo<256, 256, 2, 4, 32, 5>>(f, which, s);
-        case 7: return launch_cfg<Geo<128, 256, 1, 4, 32, 5, 0, true>>(f, which, s);
-        case 6: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true>>(f, which, s);
-        case 8: return launch_cfg<Geo<128, 256, 2, 4, 32, 5, 4, true, 16>>(f, which, s);
-        case 9: return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true, 16>>(f, which, s);
-        default:
-            return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true, 16>, Geo<128, 256, 2, 4, 32, 5, 4, true, 16>>(
-                f, which, s);
-    }
+    if ((long long)f.d.T * f.d.k <= 128ll * f.d.n_ffn)
+        return launch_cfg<Geo<128, 256, 1, 4, 32, 5, 0, true>>(f, which, s);
+    if (f.no_tail) return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true, 16>>(f, which, s);
+    return launch_cfg<Geo<256, 256, 2, 4, 32, 5, 4, true, 16>, Geo<128, 256, 2, 4, 32, 5, 4, true, 16>>(
+        f, which, s);
 }
 
 }  // namespace moepp

@@ -17,7 +17,7 @@ struct moepp_ctx {
     Workspace ws;
     size_t ws_bytes;
     const float *bias;
-    int variant;          // 0 auto, 1 generic, 2 require MFMA
+    int variant;          // 0 auto, 1 generic, 2 require MFMA, 3 as 2 without the GEMM tail launch
     CapArgs cap;          // expert capacities (Eq.8); cap.on = false: unlimited
     double bal_tau;       // > 0: collect the load-balance statistics (Eq.7) with this tau
     const float *last_out_gate;   // logits of the last routed call (read by the statistics)
@@ -143,12 +143,12 @@ void clear_timing(moepp_ctx *c) {
 
 bool use_mfma_router(const moepp_ctx *c, const Dims &d, moepp_status *st) {
     const bool ok = c->desc.act == MOEPP_BF16 && router_mfma_supported(d);
-    if (c->variant == 2 && !ok) *st = MOEPP_EUNSUPPORTED;
+    if (c->variant >= 2 && !ok) *st = MOEPP_EUNSUPPORTED;
     return ok && c->variant != 1;
 }
 bool use_mfma_ffn(const moepp_ctx *c, const Dims &d, moepp_status *st) {
     const bool ok = c->desc.act == MOEPP_BF16 && ffn_mfma_supported(d);
-    if (c->variant == 2 && !ok) *st = MOEPP_EUNSUPPORTED;
+    if (c->variant >= 2 && !ok) *st = MOEPP_EUNSUPPORTED;
     return ok && c->variant != 1;
 }
 
@@ -244,6 +244,7 @@ moepp_status do_ffn(moepp_ctx *c, hipStream_t s, int T, const void *x, const voi
     a.h = c->ws.h;
     a.yffn = c->ws.yffn;
     a.h_rows = c->desc.T_max * c->desc.k;
+    a.no_tail = c->variant == 3;
     const bool bf = c->desc.act == MOEPP_BF16;
     hipError_t e;
     {
@@ -372,19 +373,22 @@ moepp_status moepp_set_router_bias(moepp_ctx *ctx, const float *bias) {
 }
 
 moepp_status moepp_capacity(const moepp_desc *desc, int32_t T, int32_t k, double gamma, double tau,
-                            int32_t *cap_host) {
+                            int32_t per_assignment, int32_t *cap_host) {
     moepp_status st = check_desc(desc);
     if (st != MOEPP_OK) return st;
     if (!cap_host || T < 0 || T > desc->T_max || k < 1 || k > desc->k) return MOEPP_EINVAL;
     if (!(gamma > 0.0) || !(tau > 0.0) || !isfinite(gamma) || !isfinite(tau)) return MOEPP_EINVAL;
     const int N = n_experts(desc);
-    const double S = (double)T * (double)k;                     // assignments
-    const double den = tau * (double)desc->n_ffn + (double)(N - desc->n_ffn);
+    const double units = per_assignment ? (double)T * (double)k : (double)T;
+    // places per unit of eta: gamma * S / (tau N_FFN + N_ZC); an FFN expert gets tau of them
+    const double per_eta = gamma * units / (tau * (double)desc->n_ffn + (double)(N - desc->n_ffn));
     for (int i = 0; i < N; ++i) {
-        const double c = i < desc->n_ffn ? gamma * tau * S / den : gamma * S / den;
-        // rounded up; a value above an integer only by the representation
-        // error of gamma and tau counts as that integer
-        const double r = ceil(c - 1e-9 * (c > 1.0 ? c : 1.0));
+        const double c = i < desc->n_ffn ? tau * per_eta : per_eta;
+        // the next integer at or above c; a c that sits above an integer only by the
+        // representation error of gamma and tau (relative 1e-9) is that integer
+        const double near = nearbyint(c);
+        const double tol = 1e-9 * (c > 1.0 ? c : 1.0);
+        const double r = (c > near && c - near <= tol) ? near : ceil(c);
         cap_host[i] = r > 2147483647.0 ? 2147483647 : (int32_t)r;
     }
     return MOEPP_OK;
@@ -427,7 +431,7 @@ moepp_status moepp_get_kept(moepp_ctx *ctx, const int32_t **kept) {
 }
 
 moepp_status moepp_set_variant(moepp_ctx *ctx, int32_t variant) {
-    if (!ctx || variant < 0 || variant > 2) return MOEPP_EINVAL;
+    if (!ctx || variant < 0 || variant > 3) return MOEPP_EINVAL;
     ctx->variant = variant;
     return MOEPP_OK;
 }

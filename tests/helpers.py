@@ -15,31 +15,11 @@ from __future__ import annotations
 import numpy as np
 
 import oracle
+from paper_2410_07348_amd.torch_util import make_layer, to_device  # noqa: F401  (re-exported)
 
 MARGIN = 1e-4
 TOL_OUT = {"bf16": 1e-2, "f32": 1e-5}
 TOL_F32 = 1e-5
-
-
-def to_device(shape, inp, device="cuda:0"):
-    import torch
-    act = torch.bfloat16 if shape.act == "bf16" else torch.float32
-    dev = {}
-    for name, a in inp.items():
-        if a is None:
-            dev[name] = None
-            continue
-        t = torch.from_numpy(np.ascontiguousarray(a))
-        if name in ("x", "w1", "w3", "w2", "const_vecs"):
-            t = t.to(act)
-        dev[name] = t.to(device)
-    return dev
-
-
-def make_layer(shape, device="cuda:0", T_max=None):
-    import paper_2410_07348_amd as M
-    return M.Layer(T_max or max(shape.T, 1), shape.D, shape.F, shape.n_ffn, shape.n_zero,
-                   shape.n_copy, shape.n_const, k=shape.k, act=shape.act, device=device)
 
 
 def gpu_forward(shape, inp, variant=0, layer=None, dev=None, intermediates=True, cap=None,

@@ -134,7 +134,7 @@ def test_step_calls_reject_bad_arguments(L, ctx):
     assert L.moepp_expert_ffn(ctx, None, 16, fake(), None, 2) == B.EINVAL
     assert L.moepp_combine(ctx, None, 16, fake(), fake(), 2, None) == B.EINVAL
     assert L.moepp_combine(ctx, None, 16, fake(), None, 2, fake()) == B.EINVAL
-    assert L.moepp_set_variant(ctx, 3) == B.EINVAL
+    assert L.moepp_set_variant(ctx, 4) == B.EINVAL
     assert L.moepp_set_variant(ctx, 1) == B.OK
     assert L.moepp_set_router_bias(ctx, fake(0x10004)) == B.EINVAL
     assert L.moepp_set_router_bias(ctx, None) == B.OK
@@ -191,8 +191,11 @@ def test_mfma_ceiling_argument_checks(L):
 
 
 def test_capacity_is_host_arithmetic_and_matches_the_oracle(L):
-    """moepp_capacity needs no GPU; Eq.8 in the library and in the oracle are
-    two independent implementations of the same formula."""
+    """moepp_capacity needs no GPU.  The library and the oracle evaluate the same
+    formula (Eq.8) with the same rounding rule; what pins the formula itself is
+    the exact rational arithmetic of tests/test_oracle_capacity_pins.py, this
+    test only shows that the library agrees with the pinned oracle in both
+    readings of S (assignments, tokens)."""
     import oracle
     from types import SimpleNamespace as NS
     for T, k, nf, nz, nc, nk, gamma, tau in [(256, 2, 4, 1, 1, 2, 1.1, 0.75), (100, 2, 8, 4, 0, 0, 1.1, 0.75),
@@ -202,21 +205,22 @@ def test_capacity_is_host_arithmetic_and_matches_the_oracle(L):
         d = desc(T_max=max(T, 1), n_ffn=nf, n_zero=nz, n_copy=nc, n_const=nk, k=k)
         N = nf + nz + nc + nk
         cap = (ctypes.c_int32 * N)()
-        assert L.moepp_capacity(byref(d), T, k, gamma, tau, cap) == B.OK
         sh = NS(T=T, D=64, F=96, n_ffn=nf, n_zero=nz, n_copy=nc, n_const=nk, k=k)
-        assert list(cap) == oracle.capacity(sh, gamma, tau).tolist(), (T, k, nf, gamma, tau)
+        for per in (1, 0):
+            assert L.moepp_capacity(byref(d), T, k, gamma, tau, per, cap) == B.OK
+            assert list(cap) == oracle.capacity(sh, gamma, tau, bool(per)).tolist(), (T, k, nf, gamma, tau, per)
 
 
 def test_capacity_and_balance_argument_checks(L, ctx):
     d = desc()
     cap = (ctypes.c_int32 * 8)()
-    assert L.moepp_capacity(None, 16, 2, 1.1, 0.75, cap) == B.EINVAL
-    assert L.moepp_capacity(byref(d), 16, 2, 1.1, 0.75, None) == B.EINVAL
-    assert L.moepp_capacity(byref(d), 129, 2, 1.1, 0.75, cap) == B.EINVAL      # > T_max
-    assert L.moepp_capacity(byref(d), 16, 3, 1.1, 0.75, cap) == B.EINVAL       # > desc.k
-    assert L.moepp_capacity(byref(d), 16, 2, 0.0, 0.75, cap) == B.EINVAL
-    assert L.moepp_capacity(byref(d), 16, 2, 1.1, -1.0, cap) == B.EINVAL
-    assert L.moepp_capacity(byref(d), 16, 2, float("nan"), 0.75, cap) == B.EINVAL
+    assert L.moepp_capacity(None, 16, 2, 1.1, 0.75, 1, cap) == B.EINVAL
+    assert L.moepp_capacity(byref(d), 16, 2, 1.1, 0.75, 1, None) == B.EINVAL
+    assert L.moepp_capacity(byref(d), 129, 2, 1.1, 0.75, 1, cap) == B.EINVAL      # > T_max
+    assert L.moepp_capacity(byref(d), 16, 3, 1.1, 0.75, 1, cap) == B.EINVAL       # > desc.k
+    assert L.moepp_capacity(byref(d), 16, 2, 0.0, 0.75, 1, cap) == B.EINVAL
+    assert L.moepp_capacity(byref(d), 16, 2, 1.1, -1.0, 1, cap) == B.EINVAL
+    assert L.moepp_capacity(byref(d), 16, 2, float("nan"), 0.75, 1, cap) == B.EINVAL
     assert L.moepp_set_capacity(None, cap) == B.EINVAL
     bad = (ctypes.c_int32 * 8)(1, 2, -1, 4, 5, 6, 7, 8)
     assert L.moepp_set_capacity(ctx, bad) == B.EINVAL

@@ -1,11 +1,15 @@
 """Several MoE++ layers back to back: the routing logits G(x^j) of one layer are
 the gating residual input of the next (Eq.6), the first layer has none.  Checked
-against the oracle run the same way, eagerly and as one captured HIP graph."""
+against the oracle run the same way, eagerly and as one captured HIP graph.  In
+the first test every layer sees the same tokens (only the gate path is
+chained); in the second the output y^j of a layer is the input x^{j+1} of the
+next as well."""
 import numpy as np
 import pytest
 
 import oracle
 from workloads import LayerShape, make_inputs
+from workloads.gen import round_to_bf16
 
 from helpers import TOL_F32, TOL_OUT, make_layer, rel_err, to_device
 
@@ -107,3 +111,96 @@ def test_chain_of_layers_eager_and_as_one_graph(kw):
         Ls[0].layer_forward(x, None, devs[0]["W_g"], None, packed[0], devs[0]["const_vecs"],
                             devs[0]["W_c"], k=s.k)
         torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------
+# y^j -> x^{j+1} as well
+#
+# The GPU rounds h, yffn and y to bf16, the oracle does not, so from the second
+# layer on the two chains see inputs that differ by bf16 rounding (relative
+# ~2^-9 per element) and are no longer comparable to float32 accuracy:
+#  * layer 1 (identical inputs) is held to the usual tolerances;
+#  * the oracle's y^j is rounded to bf16 (the type the next layer reads) before
+#    it becomes x^{j+1}; from layer 2 on out_gate is compared to twice the bf16
+#    tolerance (the logits are linear in an x that carries the three bf16
+#    roundings of the layer before) and `out` to j bf16 tolerances at layer j,
+#    on the tokens that both chains have routed alike in every layer so far;
+#  * a token near a Top-K boundary may be routed differently once its logits
+#    differ by input rounding: such a token must be rare, and the GPU's selection
+#    must be the exact Top-K (lower index on ties, descending order) of the
+#    logits the GPU itself returned for it, i.e. a valid routing of its input.
+def topk_of(logits, k):
+    order = np.lexsort((np.arange(logits.shape[1])[None, :].repeat(logits.shape[0], 0), -logits), axis=1)
+    return order[:, :k]
+
+
+@pytest.mark.parametrize("kw", [dict(T=300, D=256, F=384, n_ffn=5), dict(T=2500, D=512, F=256, n_ffn=6)])
+def test_chain_in_which_a_layers_output_is_the_next_layers_input(kw):
+    import torch
+    base = dict(T=300, D=256, F=384, n_ffn=5, n_zero=1, n_copy=1, n_const=2, k=2, act="bf16", seed=900)
+    base.update(kw)
+    s = LayerShape("xchain", **base)
+    layers = [make_inputs(s.with_(seed=s.seed + 10 * j)) for j in range(J)]
+    layers[0]["prev_gate"] = layers[0]["W_res"] = None          # Eq.6, j = 1
+    devs = [to_device(s, dict(lay, prev_gate=None)) for lay in layers]
+    Ls = [make_layer(s) for _ in range(J)]
+    packed = [L.pack_experts(d["w1"], d["w3"], d["w2"]) for L, d in zip(Ls, devs)]
+    outs = [torch.empty((s.T, s.D), dtype=Ls[0].act_dtype, device="cuda:0") for _ in range(J)]
+    gates = [torch.empty((s.T, s.N), dtype=torch.float32, device="cuda:0") for _ in range(J)]
+
+    def run_chain():
+        for j in range(J):
+            d = devs[j]
+            Ls[j].layer_forward(devs[0]["x"] if j == 0 else outs[j - 1], gates[j - 1] if j else None,
+                                d["W_g"], d["W_res"] if j else None, packed[j], d["const_vecs"],
+                                d["W_c"], k=s.k, out=outs[j], out_gate=gates[j])
+
+    say("x-chain eager", kw)
+    run_chain()
+    torch.cuda.synchronize()
+    g_out = [o.float().cpu().numpy().astype(np.float64) for o in outs]
+    g_gate = [g.cpu().numpy() for g in gates]
+    g_idx = [L.get_routing()["topk_idx"].cpu().numpy().copy() for L in Ls]
+    eager_out = [o.clone() for o in outs]
+
+    # the oracle chain on its own outputs
+    x, prev = layers[0]["x"], None
+    alike = np.ones(s.T, bool)
+    for j, lay in enumerate(layers):
+        r = oracle.layer_forward(s, dict(lay, x=x, prev_gate=prev))
+        tol_gate = TOL_F32 if j == 0 else 2 * TOL_OUT["bf16"]
+        tol_out = TOL_OUT["bf16"] * (j + 1)
+        # (a token that was routed differently in an earlier layer has another input here)
+        e_g = rel_err(g_gate[j][alike], r["out_gate"][alike])
+        same = (g_idx[j] == r["topk_idx"]).all(axis=1)
+        # a differing token's GPU selection is the Top-K of the GPU's own logits
+        assert np.array_equal(topk_of(g_gate[j][~same], s.k), g_idx[j][~same]), j
+        newly = alike & ~same
+        alike &= same
+        e_o = rel_err(g_out[j][alike], r["out"][alike])
+        say("layer", j, "out_gate", e_g, "newly routed differently", int(newly.sum()),
+            "alike so far", int(alike.sum()), "of", s.T, "out", e_o)
+        assert e_g <= tol_gate and e_o <= tol_out
+        assert newly.mean() <= (0.0 if j == 0 else 0.03) + 2.0 / s.T, j
+        x = round_to_bf16(np.ascontiguousarray(r["out"], dtype=np.float32))
+        prev = r["out_gate"]
+    assert alike.mean() >= 0.9
+
+    # the same chain as one graph: bit-identical to the eager run on every replay
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        run_chain()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run_chain()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(2):
+        for o in outs:
+            o.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for j in range(J):
+            assert torch.equal(outs[j], eager_out[j]), (rep, j)

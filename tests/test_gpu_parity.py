@@ -155,10 +155,9 @@ def test_workload_mid_with_the_papers_capacity_sampled():
     L = make_layer(s)
     cap = L.capacity(s.T, 1.1, 0.75)
     assert cap == oracle.capacity(s, 1.1, 0.75).tolist()
-    res = gpu_forward(s, inp, variant=2, layer=L, cap=cap, balance_tau=0.75, intermediates=False)
-    toks = sample_tokens(s, res["topk_idx"], 256, seed=9)
-    errs = check_layer(s, inp, res, tok_list=toks, cap=np.array(cap, np.int32), balance_tau=0.75,
-                       check_inter=False)
+    res = gpu_forward(s, inp, variant=2, layer=L, cap=cap, balance_tau=0.75)
+    toks = sample_tokens(s, res["topk_idx"], 4096, seed=9)
+    errs = check_layer(s, inp, res, tok_list=toks, cap=np.array(cap, np.int32), balance_tau=0.75)
     say("mid with capacity", errs, "kept", res["kept"].tolist())
     assert errs["dropped"] > 0
 
@@ -315,15 +314,13 @@ def test_mfma_and_generic_kernels_agree():
     assert rel_err(b["out"][same], a["out"][same]) <= 1e-2
 
 
-def test_gemm_tail_launch_is_bitwise_the_single_launch(monkeypatch):
+def test_gemm_tail_launch_is_bitwise_the_single_launch():
     """A problem of a few rounds of tiles whose last round is sparsely filled is
     finished by a second launch with half-height tiles: same bits as one launch,
     and right against the oracle."""
     s = small_shape("tail", T=9000, D=512, F=1024, n_ffn=5, seed=131)
     inp = make_inputs(s)
-    monkeypatch.setenv("MOEPP_GEMM_CFG", "9")        # the default geometry without the tail launch
-    a = gpu_forward(s, inp, variant=2)
-    monkeypatch.delenv("MOEPP_GEMM_CFG")
+    a = gpu_forward(s, inp, variant=3)               # the default geometry without the tail launch
     b = gpu_forward(s, inp, variant=2)
     m_tiles = int(sum(-(-int(c) // 256) for c in b["counts"][:s.n_ffn]))
     left1, left2 = m_tiles * (2 * s.F // 256) % 256, m_tiles * (s.D // 256) % 256
@@ -335,32 +332,46 @@ def test_gemm_tail_launch_is_bitwise_the_single_launch(monkeypatch):
 
 
 # ------------------------------------------------- the benchmark's own shapes
-def _full_size(name, n_sample, check_inter=True):
+def _full_size(name, n_sample, check_inter=True, capacity=None):
+    """One forward of a benchmark workload with the kernels bench.py times
+    (variant 2: the MFMA kernels must cover every benchmark shape), compared
+    with the oracle: routing, counts and the permutation on all tokens, out / h /
+    yffn on all tokens (n_sample None) or on a seeded sample that covers every
+    selected expert.  capacity = (gamma, tau): Eq.8 capacities and Eq.7 statistics on."""
     s = WORKLOADS[name]
     say("workload", name, s)
     inp = make_inputs(s)
     say("inputs ready")
-    res = gpu_forward(s, inp, variant=2)      # the MFMA kernels must cover every benchmark shape
-    say("gpu done, R =", int(res["offsets"][-1]), "counts", res["counts"].tolist())
+    L = make_layer(s)
+    cap, tau = None, 0.0
+    if capacity:
+        cap = L.capacity(s.T, capacity[0], capacity[1])
+        assert cap == oracle.capacity(s, capacity[0], capacity[1]).tolist()
+        tau = capacity[1]
+    res = gpu_forward(s, inp, variant=2, layer=L, cap=cap, balance_tau=tau,
+                      intermediates=check_inter)
+    say("gpu done, R =", int(res["offsets"][-1]), "counts", res["counts"].tolist(),
+        "kept", res["kept"].tolist())
     toks = None if n_sample is None else sample_tokens(s, res["topk_idx"], n_sample, seed=s.seed)
-    errs = check_layer(s, inp, res, tok_list=toks, check_inter=check_inter)
+    errs = check_layer(s, inp, res, tok_list=toks, check_inter=check_inter,
+                       cap=None if cap is None else np.array(cap, np.int32), balance_tau=tau)
     say(name, "errs", errs)
     return s, res, errs
 
 
 def test_workload_small_all_tokens():
-    s, res, errs = _full_size("small", None, check_inter=False)
+    s, res, errs = _full_size("small", None)
     assert abs(errs["R"] / (s.T * s.k) - s.n_ffn / s.N) < 0.01      # Tab.1 with tau = 1
 
 
-def test_workload_mid_ragged_groups_sampled():
-    s, res, errs = _full_size("mid", 4096)
+def test_workload_mid_ragged_groups_all_tokens():
+    s, res, errs = _full_size("mid", None)
     c = res["counts"][:s.n_ffn]
     assert c.max() > 8 * max(c.min(), 1)
 
 
-def test_workload_skew_sampled():
-    s, res, errs = _full_size("skew", 4096)
+def test_workload_skew_all_tokens():
+    s, res, errs = _full_size("skew", None)
     c = res["counts"].astype(np.float64)
     assert abs(c[s.n_ffn:].sum() / c.sum() - 0.5) < 0.03
     assert abs(c[0] / c[1:s.n_ffn].mean() - 4.0) < 0.5
@@ -375,11 +386,18 @@ def test_workload_large_sampled():
     assert abs(errs["R"] / (s.T * s.k) - s.n_ffn / s.N) < 0.01
 
 
+def test_workload_large_with_the_papers_capacity_sampled():
+    """The large layer as bench.py times it a second time: capacities of Eq.8 at
+    gamma = 1.1, tau = 0.75 and the statistics of Eq.7 on."""
+    s, res, errs = _full_size("large", 4096, capacity=(1.1, 0.75))
+    assert errs["dropped"] > 0 and np.all(res["kept"] <= res["counts"])
+
+
 def test_workload_large_two_kernel_families_all_tokens():
     """Every token of the benchmark workload through both kernel families (plain
     fp32 FMA kernels and the MFMA kernels): same routing except inside float32
-    noise, outputs within the bf16 tolerance.  Extends the sampled oracle check
-    above to all 32768 tokens."""
+    noise, outputs within the bf16 tolerance.  A consistency check between two
+    HIP paths over all 32768 tokens; the oracle comparison is the sampled test above."""
     s = WORKLOADS["large"]
     inp = make_inputs(s)
     L = make_layer(s)
@@ -394,7 +412,8 @@ def test_workload_large_two_kernel_families_all_tokens():
     assert rel_err(b["topk_w"][same], a["topk_w"][same]) <= 1e-5
 
 
-def test_workload_large_vanilla_sampled():
-    """The vanilla comparison layer of the benchmark (20 FFN experts, none other)."""
-    s, res, errs = _full_size("large_vanilla20", 1024, check_inter=False)
+@pytest.mark.parametrize("name", ["large_vanilla20", "large_vanilla16"])
+def test_workload_large_vanilla_sampled(name):
+    """The vanilla comparison layers of the benchmark (20 or 16 FFN experts, none other)."""
+    s, res, errs = _full_size(name, 4096)
     assert errs["R"] == s.T * s.k

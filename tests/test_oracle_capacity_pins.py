@@ -36,6 +36,9 @@ def test_eq8_at_the_papers_defaults(golden):
     cap = oracle.capacity(sh, 1.1, 0.75)
     assert set(cap[:16]) == {int(g["EQ8.c_ffn"][0][0])}
     assert set(cap[16:]) == {int(g["EQ8.c_zc"][0][0])}
+    lit = oracle.capacity(sh, 1.1, 0.75, per_assignment=False)
+    assert set(lit[:16]) == {int(g["EQ8.lit_c_ffn"][0][0])}
+    assert set(lit[16:]) == {int(g["EQ8.lit_c_zc"][0][0])}
 
 
 @pytest.mark.parametrize("T,k,n_ffn,n_zc,gamma,tau", [
@@ -54,6 +57,11 @@ def test_eq8_in_exact_rational_arithmetic(T, k, n_ffn, n_zc, gamma, tau):
     # tau is the ratio between the two kinds (up to the rounding)
     if n_zc and n_ffn:
         assert abs(int(cap[0]) - tau * int(cap[-1])) < 1 + tau
+    # Eq.8 as it is printed, with the number of tokens T in place of the assignments
+    lit = oracle.capacity(sh, float(gamma), float(tau), per_assignment=False)
+    assert all(int(c) == math.ceil(gamma * tau * T / den) for c in lit[:n_ffn])
+    assert all(int(c) == math.ceil(gamma * T / den) for c in lit[n_ffn:])
+    assert gamma * T <= int(lit.sum()) < gamma * T + (n_ffn + n_zc)
 
 
 def test_without_zero_computation_experts_it_is_the_textbook_capacity():
