@@ -299,7 +299,8 @@ moepp_status moepp_set_variant(moepp_ctx *ctx, int32_t variant);
 moepp_status moepp_mfma_ceiling(void *stream, void *scratch, size_t scratch_bytes,
                                 int32_t iters, double *flops);
 
-const char *moepp_status_str(moepp_status status);
+/* Text of a status code (any integer: unknown values give "unknown status"). */
+const char *moepp_status_str(int32_t status);
 
 #ifdef __cplusplus
 }

@@ -297,6 +297,57 @@ moepp_status check_route_args(const moepp_ctx *c, const void *x, const float *pr
     return MOEPP_OK;
 }
 
+// Argument checks of moepp_layer_forward for T > 0 (nothing is launched).
+moepp_status check_forward(const moepp_ctx *ctx, int32_t T, const void *x, const float *prev_gate,
+                           const float *W_g, const float *W_res, const void *experts,
+                           const void *const_vecs, const float *W_c, int32_t k, const void *out,
+                           const float *out_gate) {
+    moepp_status st = check_route_args(ctx, x, prev_gate, W_g, W_res, W_c, out_gate);
+    if (st != MOEPP_OK) return st;
+    if (!out || misaligned(out)) return MOEPP_EINVAL;
+    if (ctx->desc.n_ffn > 0 && (!experts || misaligned(experts))) return MOEPP_EINVAL;
+    if (ctx->desc.n_const > 0 && (!const_vecs || misaligned(const_vecs))) return MOEPP_EINVAL;
+    // a required kernel family that does not cover the shape must fail before anything is launched
+    const Dims d = dims_of(ctx, T, k);
+    moepp_status s2 = MOEPP_OK;
+    (void)use_mfma_router(ctx, d, &s2);
+    (void)use_mfma_ffn(ctx, d, &s2);
+    return s2;
+}
+
+// The four steps, arguments already checked.
+moepp_status run_forward(moepp_ctx *ctx, void *stream, int32_t T, const void *x,
+                         const float *prev_gate, const float *W_g, const float *W_res,
+                         const void *experts, const void *const_vecs, const float *W_c, int32_t k,
+                         void *out, float *out_gate) {
+    reset_ran(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    moepp_status st = do_route(ctx, s, T, x, prev_gate, W_g, W_res, W_c, k, out_gate);
+    if (st != MOEPP_OK) return st;
+    st = do_permute(ctx, s, T, k);
+    if (st != MOEPP_OK) return st;
+    st = do_ffn(ctx, s, T, x, experts, k);
+    if (st != MOEPP_OK) return st;
+    return do_combine(ctx, s, T, x, const_vecs, k, out);
+}
+
+// Fresh host-side state of a context over `workspace` (already validated).
+void init_ctx(moepp_ctx *c, const moepp_desc *desc, void *workspace) {
+    c->desc = *desc;
+    c->ws_bytes = layout(desc, (char *)workspace, &c->ws);
+    c->bias = nullptr;
+    c->variant = 0;
+    c->cap.on = false;
+    for (int i = 0; i < kMaxExperts; ++i) c->cap.cap[i] = 0;
+    c->bal_tau = 0.0;
+    c->last_out_gate = nullptr;
+    c->last_T = 0;
+    c->last_k = desc->k;
+    c->timing = false;
+    c->have_events = false;
+    clear_timing(c);
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -321,19 +372,7 @@ moepp_status moepp_create(const moepp_desc *desc, void *workspace, size_t bytes,
     if (bytes < layout(desc, nullptr, nullptr)) return MOEPP_ENOMEM;
     moepp_ctx *c = new (std::nothrow) moepp_ctx();
     if (!c) return MOEPP_ENOMEM;
-    c->desc = *desc;
-    c->ws_bytes = layout(desc, (char *)workspace, &c->ws);
-    c->bias = nullptr;
-    c->variant = 0;
-    c->cap.on = false;
-    for (int i = 0; i < kMaxExperts; ++i) c->cap.cap[i] = 0;
-    c->bal_tau = 0.0;
-    c->last_out_gate = nullptr;
-    c->last_T = 0;
-    c->last_k = desc->k;
-    c->timing = false;
-    c->have_events = false;
-    clear_timing(c);
+    init_ctx(c, desc, workspace);
     *ctx = c;
     return MOEPP_OK;
 }
@@ -486,28 +525,10 @@ moepp_status moepp_layer_forward(moepp_ctx *ctx, void *stream, int32_t T, const 
     moepp_status st = check_call(ctx, T, k);
     if (st != MOEPP_OK) return st;
     if (T == 0) return note_empty_call(ctx, k);
-    st = check_route_args(ctx, x, prev_gate, W_g, W_res, W_c, out_gate);
+    st = check_forward(ctx, T, x, prev_gate, W_g, W_res, experts, const_vecs, W_c, k, out, out_gate);
     if (st != MOEPP_OK) return st;
-    if (!out || misaligned(out)) return MOEPP_EINVAL;
-    if (ctx->desc.n_ffn > 0 && (!experts || misaligned(experts))) return MOEPP_EINVAL;
-    if (ctx->desc.n_const > 0 && (!const_vecs || misaligned(const_vecs))) return MOEPP_EINVAL;
-    // variant 2 must fail before anything is launched
-    {
-        const Dims d = dims_of(ctx, T, k);
-        moepp_status s2 = MOEPP_OK;
-        (void)use_mfma_router(ctx, d, &s2);
-        (void)use_mfma_ffn(ctx, d, &s2);
-        if (s2 != MOEPP_OK) return s2;
-    }
-    reset_ran(ctx);
-    hipStream_t s = (hipStream_t)stream;
-    st = do_route(ctx, s, T, x, prev_gate, W_g, W_res, W_c, k, out_gate);
-    if (st != MOEPP_OK) return st;
-    st = do_permute(ctx, s, T, k);
-    if (st != MOEPP_OK) return st;
-    st = do_ffn(ctx, s, T, x, experts, k);
-    if (st != MOEPP_OK) return st;
-    return do_combine(ctx, s, T, x, const_vecs, k, out);
+    return run_forward(ctx, stream, T, x, prev_gate, W_g, W_res, experts, const_vecs, W_c, k, out,
+                       out_gate);
 }
 
 moepp_status moepp_get_routing(moepp_ctx *ctx, const int32_t **topk_idx, const float **topk_w,
@@ -578,7 +599,7 @@ moepp_status moepp_mfma_ceiling(void *stream, void *scratch, size_t scratch_byte
                : MOEPP_EHIP;
 }
 
-const char *moepp_status_str(moepp_status status) {
+const char *moepp_status_str(int32_t status) {
     switch (status) {
         case MOEPP_OK: return "ok";
         case MOEPP_EINVAL: return "invalid argument";

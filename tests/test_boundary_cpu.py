@@ -238,3 +238,4 @@ def test_capacity_and_balance_argument_checks(L, ctx):
     k = c_void_p()
     assert L.moepp_get_kept(ctx, byref(k)) == B.OK and k.value
     assert L.moepp_get_kept(ctx, None) == B.EINVAL
+
