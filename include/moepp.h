@@ -151,6 +151,36 @@ moepp_status moepp_layer_forward(moepp_ctx *ctx, void *stream, int32_t T,
                                  float *out_gate);
 
 /*
+ * moepp_layer_forward for callers that cannot allocate device memory and have
+ * no workspace to bring: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments and results as
+ * moepp_layer_forward on a fresh context for `desc` (automatic kernel choice,
+ * no router bias, no capacities, no statistics, no timing), but the scratch
+ * space is an array of MOEPP_STATIC_SCRATCH_BYTES that the library holds in
+ * the memory of every GPU it runs on, from the first use of the library on
+ * that GPU until the process ends.  The call allocates and frees nothing, on
+ * the device or through any library, and keeps no state between calls.
+ * ENOMEM: moepp_workspace_bytes(desc) exceeds MOEPP_STATIC_SCRATCH_BYTES (size
+ * desc.T_max for the call: at D = 4096, F = 5632, k = 2 the limit is reached
+ * near T_max = 1000).  EHIP: the array's address on the current device could
+ * not be obtained.  Other errors as moepp_layer_forward.  All calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU (other
+ * streams, other threads) race on it, and the array keeps what the last call
+ * left (every kernel writes what it later reads, nothing needs to start at
+ * zero).  The first call on a GPU asks the runtime for the array's address on
+ * that GPU (once per GPU; the runtime may set the array up at that moment), so
+ * make one call on each GPU before capturing a graph.  moepp_get_routing and
+ * the other state queries do not apply.
+ */
+#define MOEPP_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+moepp_status moepp_layer_forward_static(const moepp_desc *desc, void *stream, int32_t T,
+                                        const void *x, const float *prev_gate,
+                                        const float *W_g, const float *W_res,
+                                        const void *experts, const void *const_vecs,
+                                        const float *W_c, int32_t k, void *out,
+                                        float *out_gate);
+
+/*
  * The four steps of moepp_layer_forward as separate calls (same argument
  * meaning).  Each reads what the previous step left in the workspace.
  *

@@ -18,7 +18,7 @@ EXPORTS = ("moepp_workspace_bytes", "moepp_packed_bytes", "moepp_create", "moepp
            "moepp_get_routing", "moepp_get_intermediates", "moepp_set_timing",
            "moepp_get_timing", "moepp_set_variant", "moepp_mfma_ceiling", "moepp_status_str",
            "moepp_capacity", "moepp_set_capacity", "moepp_get_kept", "moepp_set_balance",
-           "moepp_get_balance")
+           "moepp_get_balance", "moepp_layer_forward_static")
 
 
 class MoeppError(RuntimeError):
@@ -72,6 +72,8 @@ def load_library(build_if_missing: bool = True):
     L.moepp_set_router_bias.argtypes = [vp, f32p]
     L.moepp_layer_forward.argtypes = [vp, vp, i32, vp, f32p, f32p, f32p, vp, vp, f32p, i32,
                                       vp, f32p]
+    L.moepp_layer_forward_static.argtypes = [POINTER(Desc), vp, i32, vp, f32p, f32p, f32p, vp, vp,
+                                             f32p, i32, vp, f32p]
     L.moepp_route.argtypes = [vp, vp, i32, vp, f32p, f32p, f32p, f32p, i32, f32p]
     L.moepp_permute.argtypes = [vp, vp, i32, i32]
     L.moepp_expert_ffn.argtypes = [vp, vp, i32, vp, vp, i32]
@@ -140,6 +142,28 @@ def mfma_ceiling(iters=20000, reps=3, device="cuda:0"):
         e1.synchronize()
         best = max(best, flops.value / (e0.elapsed_time(e1) * 1e-3) / 1e12)
     return best
+
+
+STATIC_SCRATCH_BYTES = 32 << 20      # MOEPP_STATIC_SCRATCH_BYTES
+
+
+def layer_forward_static(desc, x, prev_gate, W_g, W_res, experts, const_vecs, W_c, k, out,
+                         out_gate, stream=None):
+    """moepp_layer_forward_static: the forward pass on the library's own static
+    scratch.  Every tensor, `out` and `out_gate` included, is the caller's; this
+    function allocates nothing."""
+    import torch
+    L = load_library()
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    act = torch.bfloat16 if desc.act == BF16 else torch.float32
+    dev = x.device
+    _check(L.moepp_layer_forward_static(
+        byref(desc), c_void_p(stream), x.shape[0], _ptr(x, act, dev),
+        _ptr(prev_gate, torch.float32, dev), _ptr(W_g, torch.float32, dev),
+        _ptr(W_res, torch.float32, dev), _ptr(experts, torch.uint8, dev),
+        _ptr(const_vecs, act, dev), _ptr(W_c, torch.float32, dev), k, _ptr(out, act, dev),
+        _ptr(out_gate, torch.float32, dev)), "moepp_layer_forward_static")
 
 
 class Layer:

@@ -6,6 +6,7 @@
 
 #include <math.h>
 
+#include <mutex>
 #include <new>
 
 using namespace moepp;
@@ -348,6 +349,33 @@ void init_ctx(moepp_ctx *c, const moepp_desc *desc, void *workspace) {
     clear_timing(c);
 }
 
+// ---- scratch of moepp_layer_forward_static ----------------------------------
+// One array per GPU, in that GPU's memory from the moment the library's code
+// object is loaded there until the process ends.  In host code the name
+// `scratch` is only a handle of the symbol, not a device address: the address
+// on the current device is asked for once per device and kept.
+constexpr size_t kStaticScratchBytes = MOEPP_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];       // per device; null until first asked for
+
+// Device address of `scratch` on the current device (null + status on failure).
+moepp_status static_scratch(void **ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return MOEPP_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) return MOEPP_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MOEPP_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return MOEPP_OK;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -528,6 +556,30 @@ moepp_status moepp_layer_forward(moepp_ctx *ctx, void *stream, int32_t T, const 
     st = check_forward(ctx, T, x, prev_gate, W_g, W_res, experts, const_vecs, W_c, k, out, out_gate);
     if (st != MOEPP_OK) return st;
     return run_forward(ctx, stream, T, x, prev_gate, W_g, W_res, experts, const_vecs, W_c, k, out,
+                       out_gate);
+}
+
+moepp_status moepp_layer_forward_static(const moepp_desc *desc, void *stream, int32_t T,
+                                        const void *x, const float *prev_gate, const float *W_g,
+                                        const float *W_res, const void *experts,
+                                        const void *const_vecs, const float *W_c, int32_t k,
+                                        void *out, float *out_gate) {
+    moepp_status st = check_desc(desc);
+    if (st != MOEPP_OK) return st;
+    if (layout(desc, nullptr, nullptr) > kStaticScratchBytes) return MOEPP_ENOMEM;
+    // Host-side bookkeeping of this call only: no device memory, nothing allocated.
+    static thread_local moepp_ctx c;
+    init_ctx(&c, desc, nullptr);
+    st = check_call(&c, T, k);
+    if (st != MOEPP_OK) return st;
+    if (T == 0) return MOEPP_OK;
+    st = check_forward(&c, T, x, prev_gate, W_g, W_res, experts, const_vecs, W_c, k, out, out_gate);
+    if (st != MOEPP_OK) return st;
+    void *ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != MOEPP_OK) return st;
+    init_ctx(&c, desc, ws);
+    return run_forward(&c, stream, T, x, prev_gate, W_g, W_res, experts, const_vecs, W_c, k, out,
                        out_gate);
 }
 

@@ -96,6 +96,13 @@ int main(void)
     EXPECT(moepp_get_timing(ctx, NULL) == MOEPP_EINVAL);
     EXPECT(moepp_get_timing(ctx, ms) == MOEPP_OK && ms[0] == 0.f);
 
+    /* the entry point on the library's static scratch */
+    EXPECT(moepp_layer_forward_static(&d, NULL, 16, NULL, fake, fake, fake, fake, fake, fake, 2, fake, fake) == MOEPP_EINVAL);
+    moepp_desc huge = {1 << 16, 4096, 5632, 16, 1, 1, 2, 2, MOEPP_BF16};
+    EXPECT(moepp_workspace_bytes(&huge) > MOEPP_STATIC_SCRATCH_BYTES);
+    EXPECT(moepp_layer_forward_static(&huge, NULL, 16, fake, fake, fake, fake, fake, fake, fake, 2, fake, fake) == MOEPP_ENOMEM);
+    EXPECT(moepp_layer_forward_static(&d, NULL, 0, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 2, NULL, NULL) == MOEPP_OK);
+
     EXPECT(strcmp(moepp_status_str(MOEPP_ENOMEM), "buffer too small") == 0);
     EXPECT(strcmp(moepp_status_str(-99), "unknown status") == 0);
     EXPECT(moepp_destroy(ctx) == MOEPP_OK);

@@ -239,3 +239,25 @@ def test_capacity_and_balance_argument_checks(L, ctx):
     assert L.moepp_get_kept(ctx, byref(k)) == B.OK and k.value
     assert L.moepp_get_kept(ctx, None) == B.EINVAL
 
+
+def test_static_scratch_forward_validates_before_touching_the_gpu(L):
+    """moepp_layer_forward_static: size limit, descriptor and argument checks all
+    come before the first HIP call, so they can be provoked here."""
+    def call(d, T=16, k=2, **kw):
+        a = dict(x=fake(), prev_gate=fake(), W_g=fake(), W_res=fake(), experts=fake(),
+                 const_vecs=fake(), W_c=fake(), out=fake(), out_gate=fake())
+        a.update(kw)
+        return L.moepp_layer_forward_static(byref(d), None, T, a["x"], a["prev_gate"], a["W_g"],
+                                            a["W_res"], a["experts"], a["const_vecs"], a["W_c"], k,
+                                            a["out"], a["out_gate"])
+    d = desc()
+    assert L.moepp_workspace_bytes(byref(d)) <= B.STATIC_SCRATCH_BYTES
+    assert L.moepp_layer_forward_static(None, None, 16, *([fake()] * 7), 2, fake(), fake()) == B.EINVAL
+    assert call(desc(D=60)) == B.EUNSUPPORTED
+    big = desc(T_max=1 << 16, D=4096, F=5632)
+    assert L.moepp_workspace_bytes(byref(big)) > B.STATIC_SCRATCH_BYTES
+    assert call(big) == B.ENOMEM
+    assert call(d, T=129) == B.EINVAL and call(d, T=-1) == B.EINVAL and call(d, k=3) == B.EINVAL
+    assert call(d, x=None) == B.EINVAL and call(d, out=fake(0x10004)) == B.EINVAL
+    assert call(d, prev_gate=None) == B.EINVAL
+    assert call(d, T=0, x=None, W_g=None, out=None, out_gate=None) == B.OK     # no-op, reads nothing
