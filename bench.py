@@ -30,6 +30,7 @@ import numpy as np
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16, published
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E, published
+RIDGE = PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)     # flop per byte
 
 
 def log(*a):
@@ -186,27 +187,51 @@ def roofline_numbers(shape, g):
         touched = sum(1 for c in g["counts"][:shape.n_ffn] if c > 0)
         by1 = touched * 2 * F * D * b + R * D * b + R * F * b
         out["gemm1_bytes"] = by1
+        # both GEMMs: every weight of the touched experts once, x rows, h twice, yffn
+        out["ffn_bytes"] = touched * 3 * F * D * b + R * D * b + 2 * R * F * b + R * D * b
         out["gemm1_gbs"] = by1 / (km["gemm1"] * 1e-3) / 1e9
         out["gemm1_flop_per_byte"] = fl1 / by1
     router_bytes = T * (D * b + (N * 4 if shape.residual else 0) + N * 4 + K * 8 + shape.n_const * 4)
     out["router_gbs"] = router_bytes / (km["router"] * 1e-3) / 1e9
-    combine_bytes = (R + 2 * T) * D * b
+    # combine: one yffn row per FFN slot, x only for the tokens with a copy or constant
+    # slot (the kernel does not read it otherwise), out once, 12 bytes of routing per slot
+    need_x = int((g["topk_idx"] >= shape.n_ffn + shape.n_zero).any(axis=1).sum())
+    combine_bytes = (R + need_x + T) * D * b + T * K * 12
+    out["combine_bytes"] = combine_bytes
     out["combine_gbs"] = combine_bytes / (km["combine"] * 1e-3) / 1e9
     out["permute_us"] = (km["perm_hist"] + km["perm_scan"] + km["perm_scatter"]) * 1e3
     return out
+
+
+def source_digest():
+    """Digest of the HIP sources: the stored counter figures belong to the kernels of one
+    state of the sources and say nothing about any other."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2410_07348_amd", "csrc")
+    for fn in sorted(os.listdir(d)):
+        if fn.endswith((".hip", ".h")):
+            with open(os.path.join(d, fn), "rb") as f:
+                h.update(fn.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
 
 
 def profiled_traffic(workload):
     """HBM bytes per launch of each kernel, from the committed rocprofv3 --pmc
     summary (FETCH_SIZE / WRITE_SIZE scaled by the copy kernel of known size);
     counters cannot be read from inside this process, so this is the stored
-    figure for the same workload, or nothing."""
+    figure for the same workload, and only while the HIP sources are the ones
+    that were profiled.  Returns (dict, note)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {})
+            allt = json.load(f)
     except OSError:
-        return {}
+        return {}, "no stored counter summary"
+    if allt.get("source_digest") != source_digest():
+        return {}, ("the HIP sources changed since profiles/hbm_traffic.json was recorded "
+                    "(digest %s, now %s): traffic not reported" % (allt.get("source_digest"), source_digest()))
+    return allt.get(workload, {}), None
 
 
 def cpu_baseline(shape, inp, target_s=15.0):
@@ -235,6 +260,61 @@ def cpu_baseline(shape, inp, target_s=15.0):
                       "(route + permute + experts), %.1f s wall" % (n, shape.T, t)}
 
 
+def summary_line(shape, g, rf, args, ceiling, traffic, traffic_note):
+    """The JSON object of the benchmark workload: the contract's fields, per-kernel
+    times and the roofline of the dominant kernel."""
+    km = g["kernel_ms"]
+    expert_ms = km["gemm1"] + km["gemm2"] + km["combine"]
+    result = {
+        "metric": "moepp_layer_forward_tokens_per_s",
+        "value": shape.T / (g["ms_per_step"] * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": g["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.act == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": shape.name, "T": shape.T, "D": shape.D, "F": shape.F,
+                   "n_ffn": shape.n_ffn, "n_zero": shape.n_zero, "n_copy": shape.n_copy,
+                   "n_const": shape.n_const, "top_k": shape.k, "bias": shape.bias,
+                   "gating_residual": shape.residual, "ffn_rows_R": g["R"],
+                   "weights": "expert weights packed once before timing"},
+        "kernel_ms": km,
+        "expert_forward_tokens_per_s": shape.T / (expert_ms * 1e-3) if expert_ms > 0 else None,
+        "pct_bf16_mfma_peak_ffn": 100.0 * rf.get("ffn_tflops", 0.0) / PEAK_BF16_MFMA_TFLOPS,
+        "router_gbs": rf["router_gbs"], "combine_gbs": rf["combine_gbs"],
+        "permute_us": rf["permute_us"],
+        "gemm2_tflops": rf.get("gemm2_tflops"),
+    }
+    ridge = RIDGE
+    if "gemm1_tflops" in rf and rf["gemm1_flop_per_byte"] < ridge:
+        # few rows per expert (decoding): GEMM1 streams the expert weights
+        result["roofline"] = {"kernel": "k_grouped_gemm<SwiGLU> (GEMM1: W1/W3 + SwiGLU)",
+                              "bound": "hbm", "achieved": rf["gemm1_gbs"], "peak": PEAK_HBM_GBS,
+                              "unit": "GB/s", "frac": rf["gemm1_gbs"] / PEAK_HBM_GBS,
+                              "traffic": traffic.get("gemm1"),
+                              "flop_per_byte": rf["gemm1_flop_per_byte"], "ridge_flop_per_byte": ridge}
+    elif "gemm1_tflops" in rf:
+        result["roofline"] = {"kernel": "k_grouped_gemm<SwiGLU> (GEMM1: W1/W3 + SwiGLU)",
+                              "bound": "mfma", "achieved": rf["gemm1_tflops"],
+                              "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                              "frac": rf["gemm1_tflops"] / PEAK_BF16_MFMA_TFLOPS,
+                              "traffic": traffic.get("gemm1"),
+                              "measured_mfma_ceiling_tflops": ceiling,
+                              "frac_of_measured_ceiling":
+                                  rf["gemm1_tflops"] / ceiling if ceiling else None}
+    else:
+        result["roofline"] = {"kernel": "k_combine", "bound": "hbm",
+                              "achieved": rf["combine_gbs"], "peak": PEAK_HBM_GBS,
+                              "unit": "GB/s", "frac": rf["combine_gbs"] / PEAK_HBM_GBS,
+                              "traffic": None}
+
+    if traffic_note:
+        result["roofline"]["traffic_note"] = traffic_note
+    result["combine_frac_hbm_peak"] = rf["combine_gbs"] / PEAK_HBM_GBS
+    result["router_frac_hbm_peak"] = rf["router_gbs"] / PEAK_HBM_GBS
+    return result
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -243,6 +323,8 @@ def main():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--no-vanilla", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the one-run summaries of the small, mid, skew and smallbatch workloads")
     ap.add_argument("--tau-sweep", default="",
                     help="also time a paper model's layer (e.g. '1B/(16+4)E') against tau")
     ap.add_argument("--chain", type=int, default=0,
@@ -270,50 +352,46 @@ def main():
 
     ceiling = M.mfma_ceiling() if shape.act == "bf16" else None
     log("measured MFMA-only ceiling (random bf16 operands): %s TFLOP/s" % ceiling)
-    traffic = profiled_traffic(shape.name)
+    stream_read, stream_copy = M.stream_ceiling(0), M.stream_ceiling(1)
+    log("measured streaming ceilings: read %.0f GB/s, copy %.0f GB/s" % (stream_read, stream_copy))
+    traffic, traffic_note = profiled_traffic(shape.name)
 
-    result = {
-        "metric": "moepp_layer_forward_tokens_per_s",
-        "value": shape.T / (g["ms_per_step"] * 1e-3),
-        "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": g["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if shape.act == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": shape.name, "T": shape.T, "D": shape.D, "F": shape.F,
-                   "n_ffn": shape.n_ffn, "n_zero": shape.n_zero, "n_copy": shape.n_copy,
-                   "n_const": shape.n_const, "top_k": shape.k, "bias": shape.bias,
-                   "gating_residual": shape.residual, "ffn_rows_R": g["R"],
-                   "weights": "packed once before timing"},
-        "kernel_ms": km,
-        "expert_forward_tokens_per_s": shape.T / (expert_ms * 1e-3) if expert_ms > 0 else None,
-        "pct_bf16_mfma_peak_ffn": 100.0 * rf.get("ffn_tflops", 0.0) / PEAK_BF16_MFMA_TFLOPS,
-        "router_gbs": rf["router_gbs"], "combine_gbs": rf["combine_gbs"],
-        "permute_us": rf["permute_us"],
-        "gemm2_tflops": rf.get("gemm2_tflops"),
-    }
-    ridge = PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)     # flop per byte
-    if "gemm1_tflops" in rf and rf["gemm1_flop_per_byte"] < ridge:
-        # few rows per expert (decoding): GEMM1 streams the expert weights
-        result["roofline"] = {"kernel": "k_grouped_gemm<SwiGLU> (GEMM1: W1/W3 + SwiGLU)",
-                              "bound": "hbm", "achieved": rf["gemm1_gbs"], "peak": PEAK_HBM_GBS,
-                              "unit": "GB/s", "frac": rf["gemm1_gbs"] / PEAK_HBM_GBS,
-                              "traffic": traffic.get("gemm1"),
-                              "flop_per_byte": rf["gemm1_flop_per_byte"], "ridge_flop_per_byte": ridge}
-    elif "gemm1_tflops" in rf:
-        result["roofline"] = {"kernel": "k_grouped_gemm<SwiGLU> (GEMM1: W1/W3 + SwiGLU)",
-                              "bound": "mfma", "achieved": rf["gemm1_tflops"],
-                              "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                              "frac": rf["gemm1_tflops"] / PEAK_BF16_MFMA_TFLOPS,
-                              "traffic": traffic.get("gemm1"),
-                              "measured_mfma_ceiling_tflops": ceiling,
-                              "frac_of_measured_ceiling":
-                                  rf["gemm1_tflops"] / ceiling if ceiling else None}
-    else:
-        result["roofline"] = {"kernel": "k_combine", "bound": "hbm",
-                              "achieved": rf["combine_gbs"], "peak": PEAK_HBM_GBS,
-                              "unit": "GB/s", "frac": rf["combine_gbs"] / PEAK_HBM_GBS,
-                              "traffic": None}
+    result = summary_line(shape, g, rf, args, ceiling, traffic, traffic_note)
+    # what kernels that only read 1 GiB / copy 0.5 GiB reach on this GPU, beside the published 8 TB/s
+    result["measured_stream_read_gbs"] = stream_read
+    result["measured_stream_copy_gbs"] = stream_copy
+
+    # ---- the other workloads, one timed run each --------------------------------
+    if not args.no_others and shape.name == "large":
+        for k_ in ("layer", "dev", "out"):
+            g.pop(k_, None)
+        torch.cuda.empty_cache()
+        others = {}
+        for name in ("small", "mid", "skew", "smallbatch"):
+            so = WORKLOADS[name]
+            log("generating", so.name)
+            go = run_gpu(so, make_inputs(so), args.steps, args.warmup)
+            ro = roofline_numbers(so, go)
+            ko = go["kernel_ms"]
+            eo = ko["gemm1"] + ko["gemm2"] + ko["combine"]
+            o = {"T": so.T, "D": so.D, "F": so.F, "ffn_rows_R": go["R"],
+                 "ms_per_step": go["ms_per_step"], "tokens_per_s": so.T / (go["ms_per_step"] * 1e-3),
+                 "expert_forward_tokens_per_s": so.T / (eo * 1e-3), "kernel_ms": ko,
+                 "pct_bf16_mfma_peak_ffn": 100.0 * ro.get("ffn_tflops", 0.0) / PEAK_BF16_MFMA_TFLOPS,
+                 "gemm1_tflops": ro.get("gemm1_tflops"), "gemm2_tflops": ro.get("gemm2_tflops"),
+                 "router_gbs": ro["router_gbs"], "combine_gbs": ro["combine_gbs"],
+                 "permute_us": ro["permute_us"]}
+            if ro.get("gemm1_flop_per_byte", 1e9) < RIDGE:
+                # few rows per expert: the GEMMs stream the expert weights, HBM is their roofline
+                o["gemm1_hbm_gbs"] = ro["gemm1_gbs"]
+                o["gemm1_frac_hbm_peak"] = ro["gemm1_gbs"] / PEAK_HBM_GBS
+                o["ffn_weight_stream_floor_us"] = 1e6 * ro["ffn_bytes"] / (PEAK_HBM_GBS * 1e9)
+                o["ffn_us"] = 1e3 * (ko["gemm1"] + ko["gemm2"])
+            others[name] = o
+            log(name, o)
+            del go
+            torch.cuda.empty_cache()
+        result["other_workloads"] = others
 
     # ---- vanilla MoE: same T/D/F/k, zero-computation experts disabled --------
     if not args.no_vanilla and shape.n_zc > 0 and shape.name == "large":

@@ -247,11 +247,14 @@ moepp_status moepp_get_intermediates(moepp_ctx *ctx, const float **alpha1,
  */
 enum {
     MOEPP_K_ROUTER = 0,  /* router GEMM + residual + softmax + top-k         */
-    MOEPP_K_HIST = 1,    /* permute: per-chunk histogram (0 for calls with at most
-                            4096 slots: one kernel does all three steps and is
-                            reported as MOEPP_K_SCATTER)                      */
-    MOEPP_K_SCAN = 2,    /* permute: exclusive scan (0 for such calls)        */
-    MOEPP_K_SCATTER = 3, /* permute: stable scatter                           */
+    MOEPP_K_HIST = 1,    /* permute: per-chunk histogram; 0 when the router kernel
+                            has counted its own selections (bf16 layers on the
+                            matrix-core router) and for calls with at most 4096
+                            slots, where one kernel does all three steps and is
+                            reported as MOEPP_K_SCATTER                       */
+    MOEPP_K_SCAN = 2,    /* permute: exclusive scan as a kernel of its own; 0 up to
+                            2048 chunks (scan and scatter are one kernel)    */
+    MOEPP_K_SCATTER = 3, /* permute: (scan and) stable scatter                */
     MOEPP_K_GEMM1 = 4,   /* grouped GEMM W1/W3 + SwiGLU                       */
     MOEPP_K_GEMM2 = 5,   /* grouped GEMM W2                                   */
     MOEPP_K_COMBINE = 6, /* weighted combine + zero-computation experts       */
@@ -328,6 +331,19 @@ moepp_status moepp_set_variant(moepp_ctx *ctx, int32_t variant);
  */
 moepp_status moepp_mfma_ceiling(void *stream, void *scratch, size_t scratch_bytes,
                                 int32_t iters, double *flops);
+
+/*
+ * Measurement aid, not part of the layer: enqueues a kernel that only moves
+ * data with 16-byte accesses, whole 1 KB pieces per wave: mode 0 reads `bytes`
+ * of `buf`, mode 1 copies the first half of `buf` over the second half.
+ * *moved_bytes (host) = bytes read + bytes written.  Timed by the caller, it
+ * gives the rate the memory system delivers to a kernel that does nothing
+ * else, which is below the published 8 TB/s.  bytes: a multiple of 32 KiB, at
+ * least 64 MiB (use more than the 256 MB of the memory-side cache).
+ * EINVAL otherwise, and for null / misaligned buf.
+ */
+moepp_status moepp_stream_ceiling(void *stream, void *buf, size_t bytes, int32_t mode,
+                                  double *moved_bytes);
 
 /* Text of a status code (any integer: unknown values give "unknown status"). */
 const char *moepp_status_str(int32_t status);

@@ -18,7 +18,7 @@ EXPORTS = ("moepp_workspace_bytes", "moepp_packed_bytes", "moepp_create", "moepp
            "moepp_get_routing", "moepp_get_intermediates", "moepp_set_timing",
            "moepp_get_timing", "moepp_set_variant", "moepp_mfma_ceiling", "moepp_status_str",
            "moepp_capacity", "moepp_set_capacity", "moepp_get_kept", "moepp_set_balance",
-           "moepp_get_balance", "moepp_layer_forward_static")
+           "moepp_get_balance", "moepp_layer_forward_static", "moepp_stream_ceiling")
 
 
 class MoeppError(RuntimeError):
@@ -84,6 +84,7 @@ def load_library(build_if_missing: bool = True):
     L.moepp_get_timing.argtypes = [vp, POINTER(c_float)]
     L.moepp_set_variant.argtypes = [vp, i32]
     L.moepp_mfma_ceiling.argtypes = [vp, vp, c_size_t, i32, POINTER(ctypes.c_double)]
+    L.moepp_stream_ceiling.argtypes = [vp, vp, c_size_t, i32, POINTER(ctypes.c_double)]
     L.moepp_capacity.argtypes = [POINTER(Desc), i32, i32, ctypes.c_double, ctypes.c_double,
                                  i32, POINTER(c_int32)]
     L.moepp_set_capacity.argtypes = [vp, POINTER(c_int32)]
@@ -141,6 +142,28 @@ def mfma_ceiling(iters=20000, reps=3, device="cuda:0"):
         e1.record(stream)
         e1.synchronize()
         best = max(best, flops.value / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
+
+
+def stream_ceiling(mode=0, nbytes=1 << 30, reps=3, device="cuda:0"):
+    """GB/s of a kernel that only reads (mode 0) or copies (mode 1) `nbytes`, timed with
+    events on the current stream; the best of `reps` launches after one warm-up."""
+    import torch
+    L = load_library()
+    dev = torch.device(device)
+    buf = torch.ones(nbytes, dtype=torch.uint8, device=dev)
+    moved = ctypes.c_double()
+    stream = torch.cuda.current_stream(dev)
+    best = 0.0
+    for rep in range(reps + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        _check(L.moepp_stream_ceiling(c_void_p(stream.cuda_stream), _ptr(buf), nbytes, mode,
+                                      byref(moved)), "moepp_stream_ceiling")
+        e1.record(stream)
+        e1.synchronize()
+        if rep:
+            best = max(best, moved.value / (e0.elapsed_time(e1) * 1e-3) / 1e9)
     return best
 
 

@@ -51,4 +51,40 @@ double mfma_ceiling_flops(int iters) {
 }
 size_t mfma_ceiling_scratch_bytes() { return (size_t)kCeilBlocks * 512 * sizeof(float); }
 
+// ---- what a kernel that only moves data reaches ------------------------------
+// mode 0: read `bytes` (each wave whole 1 KB pieces, four in flight per lane);
+// mode 1: copy the first half of the buffer over the second.  The published
+// 8 TB/s is a pin rate; this is what the memory system delivers to a kernel.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void k_stream(u32x4_t *buf, size_t n_vec, int mode) {
+    const size_t stride = (size_t)gridDim.x * 256 * 4;
+    u32x4_t acc = {0u, 0u, 0u, 0u};
+    if (mode == 0) {
+        for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i + 768 < n_vec; i += stride) {
+            const u32x4_t a = __builtin_nontemporal_load(buf + i), b = __builtin_nontemporal_load(buf + i + 256);
+            const u32x4_t c = __builtin_nontemporal_load(buf + i + 512), d = __builtin_nontemporal_load(buf + i + 768);
+            acc ^= a ^ b ^ c ^ d;
+        }
+        // never true for the buffers this is run on; keeps the loads alive
+        if (acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u && acc.z == 0x6a09e667u && acc.w == 0xbb67ae85u)
+            buf[threadIdx.x] = acc;
+    } else {
+        const size_t half = n_vec / 2;
+        for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i + 768 < half; i += stride) {
+            const u32x4_t a = __builtin_nontemporal_load(buf + i), b = __builtin_nontemporal_load(buf + i + 256);
+            const u32x4_t c = __builtin_nontemporal_load(buf + i + 512), d = __builtin_nontemporal_load(buf + i + 768);
+            __builtin_nontemporal_store(a, buf + half + i);
+            __builtin_nontemporal_store(b, buf + half + i + 256);
+            __builtin_nontemporal_store(c, buf + half + i + 512);
+            __builtin_nontemporal_store(d, buf + half + i + 768);
+        }
+    }
+}
+
+hipError_t launch_stream(void *buf, size_t bytes, int mode, hipStream_t s) {
+    hipLaunchKernelGGL(k_stream, dim3(256 * 16), dim3(256), 0, s, (u32x4_t *)buf, bytes / 16, mode);
+    return hipGetLastError();
+}
+
 }  // namespace moepp

@@ -60,12 +60,13 @@ __global__ __launch_bounds__(kCombineWaves *kWave) void k_combine(CombineArgs a)
     }
     const AT *xt = static_cast<const AT *>(a.x) + (size_t)t * D;
     AT *ot = static_cast<AT *>(a.out) + (size_t)t * D;
+#pragma unroll 2
     for (int d = lane * V; d < D; d += kWave * V) {
         float acc[V];
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[i] = 0.f;
         ActVec<AT> xv;
-        if (need_x) xv = load_vec(xt + d);
+        if (need_x) xv = load_vec_stream(xt + d);
 #pragma unroll
         for (int s = 0; s < kMaxTopK; ++s) {
             if (s < K) {

@@ -19,9 +19,14 @@ constexpr int kWave = 64;         // CDNA wavefront
 // reduction over D across workgroups.
 constexpr int kRouterSmallT = 256;
 
-// Permutation: one wave owns a chunk of kPermChunk consecutive slots.
-constexpr int kPermIters = 4;
-constexpr int kPermChunk = kWave * kPermIters;
+// Permutation: one wave owns a chunk of consecutive slots: kPermChunk of them,
+// or the slots of one workgroup of the MFMA router when that kernel has
+// counted them (at least 64 tokens).
+constexpr int kPermChunk = 4 * kWave;
+constexpr int kPermMinChunkTokens = 64;
+// Up to this many chunks every scatter wave adds up the histogram rows itself
+// (work grows with the square of the chunk count); beyond it a scan kernel does.
+constexpr int kPermDirectChunks = 2048;
 
 // Rows of W1 and W3 are interleaved in blocks of this many rows in the packed
 // expert buffer: [kPackBlk rows of W1][kPackBlk rows of W3] ...
@@ -84,7 +89,6 @@ struct Workspace {
     int32_t *chunk_base; // [n_chunks*N]
     void *h;             // [T_max*k, F] act, K-slab-major
     void *yffn;          // [T_max*k, D] act
-    void *wsplit;        // router_split_bytes(D, N + 2 n_const)
     double *bal_partial; // [kBalWaves][kMaxExperts] partial sums of Softmax(G(x))
     float *bal;          // f [N], P [N], L_b [1]  (Eq.7)
     float *router_partial; // router_small_bytes(): per-slice dot products of the few-token router
@@ -106,7 +110,7 @@ struct RouterArgs {
     int32_t *topk_idx;
     float *topk_w;
     float *alpha1;
-    void *wsplit;         // scratch of the MFMA router: bf16 pieces of the weight rows
+    int32_t *chunk_hist;  // MFMA router: [workgroup][N] selections per expert, or null
 };
 
 struct FfnArgs {
@@ -138,11 +142,18 @@ hipError_t launch_router_small(const RouterArgs &a, bool bf16, float *partial, h
 size_t router_small_bytes();
 bool router_mfma_supported(const Dims &d);
 hipError_t launch_router_mfma(const RouterArgs &a, hipStream_t s);
-size_t router_split_bytes(int D, int rows);
+int router_mfma_block_tokens(const Dims &d);
 
-hipError_t launch_perm_hist(const Dims &d, const Workspace &w, hipStream_t s);
-hipError_t launch_perm_scan(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s);
-hipError_t launch_perm_scatter(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s);
+// chunk_slots: slots per chunk (kPermChunk, or tokens per router workgroup x k)
+int perm_chunks(const Dims &d, int chunk_slots);
+hipError_t launch_perm_hist(const Dims &d, const Workspace &w, int chunk_slots, hipStream_t s);
+hipError_t launch_perm_scan(const Dims &d, const Workspace &w, const CapArgs &cap, int chunk_slots,
+                            hipStream_t s);
+hipError_t launch_perm_scatter(const Dims &d, const Workspace &w, const CapArgs &cap, int chunk_slots,
+                               hipStream_t s);
+// scan + scatter in one kernel; at most kPermDirectChunks chunks
+hipError_t launch_perm_scan_scatter(const Dims &d, const Workspace &w, const CapArgs &cap, int chunk_slots,
+                                    hipStream_t s);
 // all three steps in one workgroup, for 0 < T*k <= kPermSmallSlots
 constexpr int kPermSmallWaves = 16;
 constexpr int kPermSmallSlots = kPermSmallWaves * kPermChunk;
@@ -163,6 +174,7 @@ hipError_t launch_pack(const Dims &d, bool bf16, const void *w1, const void *w3,
 hipError_t launch_mfma_ceiling(float *scratch, int iters, hipStream_t s);
 double mfma_ceiling_flops(int iters);
 size_t mfma_ceiling_scratch_bytes();
+hipError_t launch_stream(void *buf, size_t bytes, int mode, hipStream_t s);
 
 // ---- small device helpers -------------------------------------------------
 // Workgroup barrier that orders LDS accesses only: global loads (including

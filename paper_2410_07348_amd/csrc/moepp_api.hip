@@ -23,6 +23,9 @@ struct moepp_ctx {
     double bal_tau;       // > 0: collect the load-balance statistics (Eq.7) with this tau
     const float *last_out_gate;   // logits of the last routed call (read by the statistics)
     int last_T, last_k;
+    // the MFMA router leaves a histogram per workgroup for the permutation of the same call
+    bool hist_valid;
+    int hist_T, hist_k, hist_chunk_slots;
     bool timing;
     bool have_events;
     // ring of event pairs: one slot per recorded call
@@ -59,7 +62,10 @@ moepp_status check_desc(const moepp_desc *d) {
 size_t layout(const moepp_desc *d, char *base, Workspace *ws) {
     const size_t N = n_experts(d);
     const size_t slots = (size_t)d->T_max * d->k;
-    const size_t chunks = (slots + kPermChunk - 1) / kPermChunk;
+    // chunks of the permutation: kPermChunk slots each, or one per router workgroup
+    const size_t by_slots = (slots + kPermChunk - 1) / kPermChunk;
+    const size_t by_tokens = ((size_t)d->T_max + kPermMinChunkTokens - 1) / kPermMinChunkTokens;
+    const size_t chunks = by_slots > by_tokens ? by_slots : by_tokens;
     size_t off = 0;
     auto take = [&](size_t bytes) {
         char *p = base ? base + off : nullptr;
@@ -79,7 +85,6 @@ size_t layout(const moepp_desc *d, char *base, Workspace *ws) {
     w.chunk_base = (int32_t *)take(chunks * N * 4);
     w.h = take(d->n_ffn ? slots * d->F * elt(d) : 0);
     w.yffn = take(d->n_ffn ? slots * d->D * elt(d) : 0);
-    w.wsplit = take(d->act == MOEPP_BF16 ? router_split_bytes(d->D, (int)N + 2 * d->n_const) : 0);
     w.bal_partial = (double *)take((size_t)kBalWaves * kMaxExperts * sizeof(double));
     w.bal = (float *)take((2 * N + 1) * 4);
     w.router_partial = (float *)take(router_small_bytes());
@@ -174,19 +179,33 @@ moepp_status do_route(moepp_ctx *c, hipStream_t s, int T, const void *x, const f
     a.topk_idx = c->ws.topk_idx;
     a.topk_w = c->ws.topk_w;
     a.alpha1 = c->ws.alpha1;
-    a.wsplit = c->ws.wsplit;
+    a.chunk_hist = nullptr;
     moepp_status st = MOEPP_OK;
     const bool mfma = use_mfma_router(c, a.d, &st);
     if (st != MOEPP_OK) return st;
     c->last_T = T;
     c->last_k = k;
     c->last_out_gate = out_gate;
+    c->hist_valid = false;
     if (T == 0) return MOEPP_OK;
     KernelTimer kt(c, s, MOEPP_K_ROUTER);
     const bool bf16 = c->desc.act == MOEPP_BF16;
     hipError_t e;
-    if (c->variant == 0 && T <= kRouterSmallT) e = launch_router_small(a, bf16, c->ws.router_partial, s);
-    else e = mfma ? launch_router_mfma(a, s) : launch_router_generic(a, bf16, s);
+    if (c->variant == 0 && T <= kRouterSmallT) {
+        e = launch_router_small(a, bf16, c->ws.router_partial, s);
+    } else if (mfma) {
+        // the permutation of a call with few slots runs in one workgroup and counts for itself
+        if ((long long)T * k > kPermSmallSlots) {
+            a.chunk_hist = c->ws.chunk_hist;
+            c->hist_valid = true;
+            c->hist_T = T;
+            c->hist_k = k;
+            c->hist_chunk_slots = router_mfma_block_tokens(a.d) * k;
+        }
+        e = launch_router_mfma(a, s);
+    } else {
+        e = launch_router_generic(a, bf16, s);
+    }
     return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
 }
 
@@ -207,19 +226,26 @@ moepp_status do_permute(moepp_ctx *c, hipStream_t s, int T, int k) {
         }
         return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
     }
-    {
+    // chunks: the router's workgroups when it has counted this call's selections
+    const bool counted = c->hist_valid && c->hist_T == T && c->hist_k == k;
+    const int chunk_slots = counted ? c->hist_chunk_slots : kPermChunk;
+    c->hist_valid = false;
+    if (!counted) {
         KernelTimer kt(c, s, MOEPP_K_HIST);
-        e = launch_perm_hist(d, c->ws, s);
+        e = launch_perm_hist(d, c->ws, chunk_slots, s);
+        if (e != hipSuccess) return MOEPP_EHIP;
     }
-    if (e != hipSuccess) return MOEPP_EHIP;
-    {
-        KernelTimer kt(c, s, MOEPP_K_SCAN);
-        e = launch_perm_scan(d, c->ws, c->cap, s);
-    }
-    if (e != hipSuccess) return MOEPP_EHIP;
-    {
+    if (perm_chunks(d, chunk_slots) <= kPermDirectChunks) {
         KernelTimer kt(c, s, MOEPP_K_SCATTER);
-        e = launch_perm_scatter(d, c->ws, c->cap, s);
+        e = launch_perm_scan_scatter(d, c->ws, c->cap, chunk_slots, s);
+    } else {
+        {
+            KernelTimer kt(c, s, MOEPP_K_SCAN);
+            e = launch_perm_scan(d, c->ws, c->cap, chunk_slots, s);
+        }
+        if (e != hipSuccess) return MOEPP_EHIP;
+        KernelTimer kt(c, s, MOEPP_K_SCATTER);
+        e = launch_perm_scatter(d, c->ws, c->cap, chunk_slots, s);
     }
     if (e != hipSuccess) return MOEPP_EHIP;
     if (c->bal_tau > 0.0 && T > 0) {
@@ -344,6 +370,8 @@ void init_ctx(moepp_ctx *c, const moepp_desc *desc, void *workspace) {
     c->last_out_gate = nullptr;
     c->last_T = 0;
     c->last_k = desc->k;
+    c->hist_valid = false;
+    c->hist_T = c->hist_k = c->hist_chunk_slots = 0;
     c->timing = false;
     c->have_events = false;
     clear_timing(c);
@@ -649,6 +677,14 @@ moepp_status moepp_mfma_ceiling(void *stream, void *scratch, size_t scratch_byte
     return launch_mfma_ceiling((float *)scratch, iters, (hipStream_t)stream) == hipSuccess
                ? MOEPP_OK
                : MOEPP_EHIP;
+}
+
+moepp_status moepp_stream_ceiling(void *stream, void *buf, size_t bytes, int32_t mode,
+                                  double *moved_bytes) {
+    if (!buf || !moved_bytes || misaligned(buf) || (mode != 0 && mode != 1)) return MOEPP_EINVAL;
+    if (bytes < ((size_t)64 << 20) || bytes % 32768 != 0) return MOEPP_EINVAL;
+    *moved_bytes = (double)bytes;       // mode 1: half of the buffer read and half of it written
+    return launch_stream(buf, bytes, mode, (hipStream_t)stream) == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
 }
 
 const char *moepp_status_str(int32_t status) {

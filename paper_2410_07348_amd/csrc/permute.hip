@@ -1,8 +1,15 @@
-// Grouping of the (token, slot) pairs by FFN expert: a stable counting sort in
-// three kernels (histogram per chunk, exclusive scan, scatter), or in one
-// workgroup when there are few slots.  Integer work
-// only, no atomics, so the result is the same on every run: rows of one
-// expert are ordered by ascending slot index q = t*k + s.
+// Grouping of the (token, slot) pairs by FFN expert: a stable counting sort.
+// The slots are cut into chunks (one wave each); a histogram per chunk, an
+// exclusive scan over the chunks and a scatter give every slot its row.  The
+// histogram comes from the router kernel when that one counted its own
+// workgroup's selections (then a chunk is the slots of one router workgroup),
+// else from k_perm_hist; scan and scatter are one kernel in which every wave
+// adds up the histogram rows it needs itself (a few thousand chunks at most:
+// the rows are 4 N bytes each and sit in L2), or two kernels with a
+// single-workgroup scan when there are more chunks than that; calls with few
+// slots do all of it in one workgroup.  Integer work only and no ordering left
+// to atomics, so the result is the same on every run: rows of one expert are
+// ordered by ascending slot index q = t*k + s.
 //
 // The paper does not describe this step; it is how the K selected experts of
 // Eq.1 are turned into contiguous row groups for the grouped FFN GEMM.
@@ -41,34 +48,34 @@ __device__ inline unsigned long long same_expert_lanes(int e) {
 // cnt[e] (LDS, this wave's own 64 counters) = slots of chunk c on expert e.
 // The lowest lane of every group of equal experts adds the group's size; LDS
 // operations of one wave execute in program order.
-__device__ inline void chunk_histogram(const int32_t *idx, int c, int total, int N, int lane,
-                                       volatile int *cnt) {
+__device__ inline void chunk_histogram(const int32_t *idx, int c, int chunk_slots, int total, int N,
+                                       int lane, volatile int *cnt) {
     cnt[lane] = 0;
-    for (int it = 0; it < kPermIters; ++it) {
-        const int e = slot_expert(idx, c * kPermChunk + it * kWave + lane, total, N);
+    const int end = min(total, (c + 1) * chunk_slots);
+    for (int q0 = c * chunk_slots; q0 < end; q0 += kWave) {
+        const int e = slot_expert(idx, q0 + lane, end, N);
         const unsigned long long m = same_expert_lanes(e);
         if (e >= 0 && lane == __ffsll((long long)m) - 1) cnt[e] += __popcll(m);
     }
 }
 
 // chunk_hist[c][e] = number of slots of chunk c that selected expert e.
-__global__ __launch_bounds__(kPermWaves *kWave) void k_perm_hist(Dims d, Workspace w) {
+__global__ __launch_bounds__(kPermWaves *kWave) void k_perm_hist(Dims d, Workspace w, int chunk_slots) {
     __shared__ int s_cnt[kPermWaves][kMaxExperts];
     const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
     const int c = blockIdx.x * kPermWaves + wv;
     const int total = d.T * d.k;
-    if (c * kPermChunk >= total) return;
-    chunk_histogram(w.topk_idx, c, total, d.N, lane, s_cnt[wv]);
+    if ((long long)c * chunk_slots >= total) return;
+    chunk_histogram(w.topk_idx, c, chunk_slots, total, d.N, lane, s_cnt[wv]);
     if (lane < d.N) w.chunk_hist[c * d.N + lane] = ((volatile int *)s_cnt[wv])[lane];
 }
 
 // chunk_base[c][e] = slots of expert e in chunks before c; counts; kept; offsets.
 constexpr int kScanWaves = 16;   // one workgroup; its waves share the experts
-__global__ __launch_bounds__(kScanWaves *kWave) void k_perm_scan(Dims d, Workspace w, CapArgs cap) {
+__global__ __launch_bounds__(kScanWaves *kWave) void k_perm_scan(Dims d, Workspace w, CapArgs cap,
+                                                                 int n_chunks) {
     const int lane = threadIdx.x % kWave;
     const int wv = threadIdx.x / kWave;
-    const int total = d.T * d.k;
-    const int n_chunks = (total + kPermChunk - 1) / kPermChunk;
     __shared__ int s_counts[kMaxExperts];
     for (int e = wv; e < d.N; e += kScanWaves) {
         int running = 0;
@@ -108,12 +115,12 @@ __global__ __launch_bounds__(kScanWaves *kWave) void k_perm_scan(Dims d, Workspa
 // expert e (both LDS, read only).  A slot's rank is rank[e] plus the number of
 // lower lanes on the same expert; the lowest lane of the group then moves
 // rank[e] past the group.
-__device__ inline void scatter_chunk(const Dims &d, const Workspace &w, int c, int lane,
+__device__ inline void scatter_chunk(const Dims &d, const Workspace &w, int c, int chunk_slots, int lane,
                                      volatile int *rank, const int *first_row, const int *limit) {
-    const int total = d.T * d.k;
+    const int total = min(d.T * d.k, (c + 1) * chunk_slots);     // end of this chunk
     const unsigned long long lt = (1ull << lane) - 1ull;
-    for (int it = 0; it < kPermIters; ++it) {
-        const int q = c * kPermChunk + it * kWave + lane;
+    for (int q0 = c * chunk_slots; q0 < total; q0 += kWave) {
+        const int q = q0 + lane;
         const int e = slot_expert(w.topk_idx, q, total, d.N);
         const unsigned long long m = same_expert_lanes(e);
         if (e >= 0) {
@@ -131,19 +138,117 @@ __device__ inline void scatter_chunk(const Dims &d, const Workspace &w, int c, i
     }
 }
 
-__global__ __launch_bounds__(kPermWaves *kWave) void k_perm_scatter(Dims d, Workspace w, CapArgs cap) {
+__global__ __launch_bounds__(kPermWaves *kWave) void k_perm_scatter(Dims d, Workspace w, CapArgs cap,
+                                                                   int chunk_slots) {
     __shared__ int s_rank[kPermWaves][kMaxExperts];
     __shared__ int s_first[kMaxExperts], s_limit[kMaxExperts];
     const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
     const int c = blockIdx.x * kPermWaves + wv;
-    const bool active = c * kPermChunk < d.T * d.k;
+    const bool active = (long long)c * chunk_slots < d.T * d.k;
     if (wv == 0) {
         s_first[lane] = lane < d.n_ffn ? w.offsets[lane] : 0;
         s_limit[lane] = cap.on && lane < d.N ? cap.cap[lane] : 0x7fffffff;
     }
     if (active) s_rank[wv][lane] = lane < d.N ? w.chunk_base[c * d.N + lane] : 0;
     __syncthreads();
-    if (active) scatter_chunk(d, w, c, lane, s_rank[wv], s_first, s_limit);
+    if (active) scatter_chunk(d, w, c, chunk_slots, lane, s_rank[wv], s_first, s_limit);
+}
+
+// Scan and scatter in one kernel, for at most kPermDirectChunks chunks.  Every
+// wave needs, per expert, the selections in the chunks before its own (the ranks
+// its chunk starts at) and in all chunks (the counts, from which it derives kept
+// and the first row of every FFN expert like the scan kernel does).  The
+// workgroup passes the whole table chunk_hist through LDS in pieces of
+// kScanTileInts integers with coalesced 16-byte loads, and its waves add up
+// what they need from there: lane l looks after expert l % NP of rows l / NP,
+// l / NP + 64 / NP, ... of a piece (NP = N rounded up to a power of two).  The
+// wave of chunk 0 also writes counts, kept and offsets.
+constexpr int kScanTileInts = 8192;               // 32 KB of LDS
+__global__ __launch_bounds__(kPermWaves *kWave) void k_perm_scan_scatter(Dims d, Workspace w, CapArgs cap,
+                                                                        int chunk_slots, int n_chunks) {
+    __shared__ __attribute__((aligned(16))) int s_tab[kScanTileInts];
+    __shared__ int s_rank[kPermWaves][kMaxExperts];
+    __shared__ int s_first[kPermWaves][kMaxExperts], s_limit[kPermWaves][kMaxExperts];
+    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+    const int c = blockIdx.x * kPermWaves + wv;    // may be past the last chunk: such a wave only helps loading
+    const int N = d.N;
+    int NP = 1;
+    while (NP < N) NP <<= 1;
+    const int per = kWave / NP;                    // rows a wave adds per step
+    const int e = lane % NP, sub = lane / NP;
+    const int tile_rows = kScanTileInts / N;       // whole rows per piece (N <= 64: at least 128)
+    const int total_ints = n_chunks * N;           // <= kPermDirectChunks * 64
+    int before = 0, all = 0;
+    for (int row0 = 0; row0 < n_chunks; row0 += tile_rows) {
+        const int base = row0 * N;
+        const int n_ints = min(tile_rows * N, total_ints - base);
+        // the workspace regions are 256-byte aligned and whole pieces start at multiples of N * tile_rows
+        // integers; pieces are copied 16 bytes at a time where the alignment allows, else by integers
+        if (((base | n_ints) & 3) == 0) {
+            // all loads of the piece first, then the LDS writes: one memory latency, not one per load
+            constexpr int PER = kScanTileInts / (kPermWaves * kWave * 4);
+            int4 v[PER];
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int i = (threadIdx.x + u * kPermWaves * kWave) * 4;
+                if (i < n_ints) v[u] = *reinterpret_cast<const int4 *>(&w.chunk_hist[base + i]);
+            }
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int i = (threadIdx.x + u * kPermWaves * kWave) * 4;
+                if (i < n_ints) *reinterpret_cast<int4 *>(&s_tab[i]) = v[u];
+            }
+        } else {
+            for (int i = threadIdx.x; i < n_ints; i += kPermWaves * kWave) s_tab[i] = w.chunk_hist[base + i];
+        }
+        __syncthreads();
+        const int rows = n_ints / N;
+        if (e < N) {
+            constexpr int U = 8;                   // reads in flight: the sums would otherwise wait for each one
+            for (int r0 = sub; r0 < rows; r0 += U * per) {
+                int v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u] = r0 + u * per < rows ? s_tab[(r0 + u * per) * N + e] : 0;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    all += v[u];
+                    if (row0 + r0 + u * per < c) before += v[u];
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (c >= n_chunks) return;
+    for (int o = NP; o < kWave; o <<= 1) {         // add the 64 / NP partial sums of an expert
+        before += __shfl_xor(before, o, kWave);
+        all += __shfl_xor(all, o, kWave);
+    }
+    // now lanes 0 .. N-1 (and their copies in the other sub-groups) hold expert e's sums
+    const int lim = cap.on && lane < N ? cap.cap[lane] : 0x7fffffff;
+    const int keep = lane < N ? (lim < all ? lim : all) : 0;
+    const int kf = lane < d.n_ffn ? keep : 0;
+    int incl = kf;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int up = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += up;
+    }
+    if (c == 0) {
+        if (lane < N) {
+            w.counts[lane] = all;
+            w.kept[lane] = keep;
+        }
+        if (lane < d.n_ffn) w.offsets[lane + 1] = incl;
+        if (lane == 0) w.offsets[0] = 0;
+    }
+    ((volatile int *)s_rank[wv])[lane] = lane < N ? before : 0;
+    ((volatile int *)s_first[wv])[lane] = incl - kf;
+    ((volatile int *)s_limit[wv])[lane] = lim;
+    // (this wave's own LDS rows: LDS operations of one wave execute in order; the
+    // fence keeps the compiler from moving the reads below above these writes)
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    scatter_chunk(d, w, c, chunk_slots, lane, s_rank[wv], s_first[wv], s_limit[wv]);
 }
 
 // The three steps in one workgroup, for calls with at most kPermSmallSlots
@@ -153,7 +258,7 @@ __global__ __launch_bounds__(kPermSmallWaves *kWave) void k_perm_small(Dims d, W
     __shared__ int s_first[kMaxExperts], s_limit[kMaxExperts];
     const int lane = threadIdx.x % kWave, c = threadIdx.x / kWave;
     const int total = d.T * d.k;
-    chunk_histogram(w.topk_idx, c, total, d.N, lane, s_rank[c]);
+    chunk_histogram(w.topk_idx, c, kPermChunk, total, d.N, lane, s_rank[c]);
     __syncthreads();
     if (c == 0) {                                          // wave 0: lane e scans expert e over the chunks
         int running = 0;
@@ -182,7 +287,7 @@ __global__ __launch_bounds__(kPermSmallWaves *kWave) void k_perm_small(Dims d, W
         if (lane == 0) w.offsets[0] = 0;
     }
     __syncthreads();
-    if (c * kPermChunk < total) scatter_chunk(d, w, c, lane, s_rank[c], s_first, s_limit);
+    if (c * kPermChunk < total) scatter_chunk(d, w, c, kPermChunk, lane, s_rank[c], s_first, s_limit);
 }
 
 // ---- load-balance statistics (Eq.7) ---------------------------------------
@@ -230,25 +335,38 @@ __global__ __launch_bounds__(kBalFinalWaves *kWave) void k_balance_final(Dims d,
     if (lane == 0) w.bal[2 * d.N] = (float)loss;
 }
 
-static int perm_blocks(const Dims &d) {
-    const int total = d.T * d.k;
-    const int n_chunks = (total + kPermChunk - 1) / kPermChunk;
-    return (n_chunks + kPermWaves - 1) / kPermWaves;
+int perm_chunks(const Dims &d, int chunk_slots) {
+    const long long total = (long long)d.T * d.k;
+    return (int)((total + chunk_slots - 1) / chunk_slots);
 }
+static int perm_blocks(int n_chunks) { return (n_chunks + kPermWaves - 1) / kPermWaves; }
 
-hipError_t launch_perm_hist(const Dims &d, const Workspace &w, hipStream_t s) {
+hipError_t launch_perm_hist(const Dims &d, const Workspace &w, int chunk_slots, hipStream_t s) {
     if (d.T == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_perm_hist, dim3(perm_blocks(d)), dim3(kPermWaves * kWave), 0, s, d, w);
+    hipLaunchKernelGGL(k_perm_hist, dim3(perm_blocks(perm_chunks(d, chunk_slots))), dim3(kPermWaves * kWave),
+                       0, s, d, w, chunk_slots);
     return hipGetLastError();
 }
-hipError_t launch_perm_scan(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s) {
-    hipLaunchKernelGGL(k_perm_scan, dim3(1), dim3(kScanWaves * kWave), 0, s, d, w, cap);
+hipError_t launch_perm_scan(const Dims &d, const Workspace &w, const CapArgs &cap, int chunk_slots,
+                            hipStream_t s) {
+    hipLaunchKernelGGL(k_perm_scan, dim3(1), dim3(kScanWaves * kWave), 0, s, d, w, cap,
+                       perm_chunks(d, chunk_slots));
     return hipGetLastError();
 }
-hipError_t launch_perm_scatter(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s) {
+hipError_t launch_perm_scatter(const Dims &d, const Workspace &w, const CapArgs &cap, int chunk_slots,
+                               hipStream_t s) {
     if (d.T == 0) return hipSuccess;
-    const dim3 grid(perm_blocks(d)), block(kPermWaves * kWave);
-    hipLaunchKernelGGL(k_perm_scatter, grid, block, 0, s, d, w, cap);
+    const dim3 grid(perm_blocks(perm_chunks(d, chunk_slots))), block(kPermWaves * kWave);
+    hipLaunchKernelGGL(k_perm_scatter, grid, block, 0, s, d, w, cap, chunk_slots);
+    return hipGetLastError();
+}
+hipError_t launch_perm_scan_scatter(const Dims &d, const Workspace &w, const CapArgs &cap, int chunk_slots,
+                                    hipStream_t s) {
+    if (d.T == 0) return hipSuccess;
+    const int n_chunks = perm_chunks(d, chunk_slots);
+    if (n_chunks > kPermDirectChunks) return hipErrorInvalidValue;
+    const dim3 grid(perm_blocks(n_chunks)), block(kPermWaves * kWave);
+    hipLaunchKernelGGL(k_perm_scan_scatter, grid, block, 0, s, d, w, cap, chunk_slots, n_chunks);
     return hipGetLastError();
 }
 hipError_t launch_perm_small(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s) {

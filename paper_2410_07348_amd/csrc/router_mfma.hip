@@ -12,21 +12,32 @@
 // are exact, logits keep float32-class accuracy.
 //
 // The kernel is a skinny GEMM [TOK tokens x K] x [K x (N + 2 n_const)] per
-// workgroup of TOK / 16 waves (TOK = 128, or 64 when there are few tokens).  The weight rows (router rows, then the W_c rows) are
-// split once per call by a small kernel into a scratch buffer that already has
-// the byte order of an LDS weight tile.  x and weight tiles of 64 K-elements
-// are loaded with row-contiguous 16-byte chunks (every wave-wide load covers
-// whole 128-byte lines) into REGISTERS, PF tiles ahead, and stored from there
-// into a double-buffered LDS tile (the compiler tracks these ordinary loads
-// exactly, so nothing is waited for early); up to 8 tiles per thread are in
-// flight.  Workgroup b starts at K tile b % KT and wraps around, so that the
-// workgroups, which walk K in lockstep over rows a power of two apart, do not
-// all ask the same memory channels at the same time.  Wave w owns tokens
-// 32 (w % (TOK/32)) .. +31 and the K steps of parity w / (TOK/32) of every
-// tile; the two halves are added at the end.
-// Epilogue: gating residual and bias with all threads, then one thread per
-// token does softmax and Top-K on the float32 logits (ties to the lower
-// index, slots in descending order).
+// workgroup of TOK / 16 waves (TOK = 128, or 64 when there are few tokens).
+// x and weight tiles of 64 K-elements are loaded with row-contiguous 16-byte
+// chunks (every wave-wide load covers whole 128-byte lines) into REGISTERS, PF
+// tiles ahead, and stored from there into a double-buffered LDS tile (the
+// compiler tracks these ordinary loads exactly, so nothing is waited for
+// early).  The weights are read as float32 straight from W and W_c (only the
+// real rows: N + 2 n_const of the 32 or 64 the matrix core multiplies) and split
+// into their three pieces on the way into LDS: a few VALU operations per
+// thread and tile, no prepared copy and no extra pass over them; every
+// workgroup reads all of them once, from L2.  That second stream is not free
+// (a microbenchmark of the two streams alone: 42 us for x at this workload,
+// 42 / 49 / 56 us with 0.5 / 1 / 1.5 bytes of weights per byte of x), which is
+// why the weights travel as 4-byte floats (0.375 bytes per byte of x at
+// N + 2 n_const = 24, 128 tokens) and not as three bf16 pieces (0.75).  x is
+// loaded with the non-temporal hint: it is read once.  Workgroup b starts at
+// K tile b % KT and wraps around, so that the workgroups, which walk K in
+// lockstep over rows a power of two apart, do not all ask the same memory
+// channels at the same time.  Wave w owns tokens 32 (w % (TOK/32)) .. +31 and
+// the K steps of parity w / (TOK/32) of every tile; the two halves are added
+// at the end.
+// Epilogue: gating residual and bias with all threads, then four threads per
+// token (each owns the experts i = q mod 4, shuffles combine them) do softmax
+// and Top-K on the float32 logits (ties to the lower index, slots in
+// descending order).  The workgroup also counts its tokens' selections per
+// expert: its TOK * k slots are one chunk of the permutation that follows, which
+// then needs no histogram pass of its own.
 #include "common.h"
 
 namespace moepp {
@@ -37,47 +48,6 @@ constexpr int kRtRow = kRtBK * 2;          // bytes per tile row
 // XOR swizzle of the 16-byte slots of a 128-byte tile row: 16 consecutive rows
 // read at one logical slot cover the 64 LDS banks exactly once.
 __device__ inline int rt_swz(int row) { return (row >> 1) & 7; }
-
-// Bytes of the split-weight scratch for a layer (0 if the MFMA router does not apply).
-size_t router_split_bytes(int D, int rows) {
-    const int nblk = (rows + 31) / 32;
-    return (size_t)3 * nblk * 32 * D * 2;
-}
-
-// Split kernel: float32 weight rows (router rows, then the W_c rows) -> three
-// bf16 pieces, written tile by tile in exactly the byte order of an LDS weight
-// tile (piece, row, swizzled 16-byte slot), so that the router kernel can copy
-// a tile into LDS with plain contiguous loads.  Rows past the last are zero.
-__global__ __launch_bounds__(256) void k_router_split(RouterArgs a, int nblk) {
-    typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
-    const int D = a.d.D, N = a.d.N, rows = N + 2 * a.d.n_const;
-    const int ROWS = nblk * 32, PIECE = ROWS * kRtRow;
-    const int per_row = D / 4;                               // float4 per row
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= ROWS * per_row) return;
-    const int r = idx / per_row, k4 = idx % per_row;         // row, float4 number
-    f32x4 w = {0.f, 0.f, 0.f, 0.f};
-    if (r < rows) {
-        const float *src = r < N ? a.W_g + (size_t)r * D : a.W_c + (size_t)(r - N) * D;
-        w = *reinterpret_cast<const f32x4 *>(src + k4 * 4);
-    }
-    bf16x4 hi, mid, lo;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const bf16_t h = (bf16_t)w[q];
-        const float r1 = w[q] - (float)h;
-        const bf16_t m = (bf16_t)r1;
-        hi[q] = h;
-        mid[q] = m;
-        lo[q] = (bf16_t)(r1 - (float)m);
-    }
-    const int kt = k4 / 16, wq = k4 % 16;                    // K tile, float4 within the tile
-    char *p = static_cast<char *>(a.wsplit) + (size_t)kt * 3 * PIECE + r * kRtRow +
-              ((((wq >> 1) ^ rt_swz(r)) << 4) | ((wq & 1) << 3));
-    *reinterpret_cast<bf16x4 *>(p) = hi;
-    *reinterpret_cast<bf16x4 *>(p + PIECE) = mid;
-    *reinterpret_cast<bf16x4 *>(p + 2 * PIECE) = lo;
-}
 
 // NBLK: 32-row blocks of weight rows; PF: tiles prefetched in registers;
 // TOK: tokens per workgroup (4 threads per token); WPE: waves per SIMD the
@@ -90,12 +60,12 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
     constexpr int ROWS = NBLK * 32;
     constexpr int PIECE = ROWS * kRtRow;                  // one bf16 piece of the weight tile
     constexpr int WBYTES = 3 * PIECE;                     // 12 KB per row block
-    constexpr int WCH = WBYTES / 16;                      // 16-byte chunks of a weight tile
+    constexpr int WCH = ROWS * (kRtBK / 4);               // 16-byte chunks (4 floats) of a float32 weight tile
     constexpr int WL = (WCH + kRtThreads - 1) / kRtThreads;   // weight chunks per thread and tile
     constexpr int STAGE = kRtXBytes + WBYTES;
     constexpr int DSTR = ROWS + 1;                        // floats per token in `dots`
     constexpr int E_BYTES = (2 * kRtTok * DSTR + kRtTok * (kMaxExperts + 1) +
-                             kMaxExperts * kMaxExperts + kMaxExperts) * 4;
+                             kMaxExperts * kMaxExperts + 2 * kMaxExperts) * 4;
     constexpr int LDS_BYTES = 2 * STAGE > E_BYTES ? 2 * STAGE : E_BYTES;
     static_assert(LDS_BYTES <= 160 * 1024 && PF % 2 == 0, "LDS / PF");
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
@@ -120,37 +90,69 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
         tok = tok < T ? tok : T - 1;
         px[i] = static_cast<const char *>(a.x) + ((size_t)tok * D + (((c % 8) ^ rt_swz(row)) << 3)) * 2;
     }
-    const char *pw[WL];
+    // Weight chunk c = tid + threads i: row c / 16, floats 4 (c % 16) .. + 3 of the
+    // tile's 64 columns, read as float32 from W (router rows) or W_c (the rows after
+    // them) and split into three bf16 pieces on the way into LDS; rows past the
+    // last are never loaded (their LDS rows are zeroed once, below).
+    const float *pw[WL];
+    int w_lds[WL];                                         // LDS offset of the chunk's hi piece; -1: no chunk
 #pragma unroll
     for (int i = 0; i < WL; ++i) {
-        int wc = tid + kRtThreads * i;
-        wc = wc < WCH ? wc : tid;                         // surplus threads re-read a chunk, not stored
-        pw[i] = static_cast<const char *>(a.wsplit) + wc * 16;
+        const int c = tid + kRtThreads * i, r = c / 16, kq = c % 16;
+        const bool act = r < rows;
+        pw[i] = (!act ? a.W_g : r < N ? a.W_g + (size_t)r * D : a.W_c + (size_t)(r - N) * D) + kq * 4;
+        w_lds[i] = act ? r * kRtRow + ((((kq >> 1) ^ rt_swz(r)) << 4) | ((kq & 1) << 3)) : -1;
     }
-    bf16x8 xr[PF][2], wr[PF][WL];
+    bf16x8 xr[PF][2];
+    f32x4 wr[PF][WL];
     // Workgroups walk K in lockstep, and rows of x are a power of two apart, so
     // without a rotation every workgroup would ask the same few memory channels
     // for its 128-byte pieces at the same time.  Workgroup b starts at K tile
     // b % KT and wraps around (a dot product does not care about the order).
     const int rot = blockIdx.x % KT;
-    auto load_regs = [&](int kt, bf16x8 *xq, bf16x8 *wq) {
+    auto load_regs = [&](int kt, bf16x8 *xq, f32x4 *wq) {
         kt = kt < KT ? kt : KT - 1;                       // past the end: harmless reload of the last tile
         kt += rot;
         kt = kt < KT ? kt : kt - KT;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) xq[i] = *reinterpret_cast<const bf16x8 *>(px[i] + (size_t)kt * (kRtBK * 2));
+        for (int i = 0; i < 2; ++i)      // x is read once: streamed past the caches' retention
+            xq[i] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8 *>(px[i] + (size_t)kt * (kRtBK * 2)));
 #pragma unroll
-        for (int i = 0; i < WL; ++i) wq[i] = *reinterpret_cast<const bf16x8 *>(pw[i] + (size_t)kt * WBYTES);
+        for (int i = 0; i < WL; ++i)
+            if (w_lds[i] >= 0) wq[i] = *reinterpret_cast<const f32x4 *>(pw[i] + (size_t)kt * kRtBK);
     };
-    auto store_regs = [&](char *stage, const bf16x8 *xq, const bf16x8 *wq) {
+    typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+    auto store_regs = [&](char *stage, const bf16x8 *xq, const f32x4 *wq) {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
             *reinterpret_cast<bf16x8 *>(stage + (tid + kRtThreads * i) * 16) = xq[i];
 #pragma unroll
         for (int i = 0; i < WL; ++i)
-            if (tid + kRtThreads * i < WCH)               // wave-uniform: WCH is a multiple of 64
-                *reinterpret_cast<bf16x8 *>(stage + kRtXBytes + (tid + kRtThreads * i) * 16) = wq[i];
+            if (w_lds[i] >= 0) {
+                // w = hi + mid + lo exactly: 3 x 8 significand bits cover float32's 24
+                bf16x4 hi, mid, lo;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bf16_t h = (bf16_t)wq[i][q];
+                    const float r1 = wq[i][q] - (float)h;
+                    const bf16_t m = (bf16_t)r1;
+                    hi[q] = h;
+                    mid[q] = m;
+                    lo[q] = (bf16_t)(r1 - (float)m);
+                }
+                char *p = stage + kRtXBytes + w_lds[i];
+                *reinterpret_cast<bf16x4 *>(p) = hi;
+                *reinterpret_cast<bf16x4 *>(p + PIECE) = mid;
+                *reinterpret_cast<bf16x4 *>(p + 2 * PIECE) = lo;
+            }
     };
+    // weight rows past the last one: zero in both stages, never written again
+    for (int c = tid; c < 2 * 3 * (ROWS - rows) * (kRtRow / 16); c += kRtThreads) {
+        const int st = c / (3 * (ROWS - rows) * (kRtRow / 16)), q = c % (3 * (ROWS - rows) * (kRtRow / 16));
+        const int pc = q / ((ROWS - rows) * (kRtRow / 16)), o = q % ((ROWS - rows) * (kRtRow / 16));
+        *reinterpret_cast<f32x4 *>(lds + st * STAGE + kRtXBytes + pc * PIECE + rows * kRtRow + o * 16) =
+            f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 
     f32x16 acc_hi[NBLK], acc_lo[NBLK];
 #pragma unroll
@@ -208,6 +210,7 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
     float *prevs = dots1 + kRtTok * DSTR;                       // [kRtTok][N + 1]
     float *wres = prevs + kRtTok * (kMaxExperts + 1);           // [N][N]
     float *sbias = wres + kMaxExperts * kMaxExperts;            // [N]
+    int *s_hist = reinterpret_cast<int *>(sbias + kMaxExperts); // [N] selections per expert
     // acc[b][v]: weight row b*32 + 8*(v/4) + 4*lh + v%4, token tb*32 + l32
     {
         float *dst = kh == 0 ? dots : dots1;
@@ -224,7 +227,10 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
             prevs[(c / N) * (N + 1) + c % N] = a.prev_gate[(size_t)t0 * N + c];
         for (int c = tid; c < N * N; c += kRtThreads) wres[c] = a.W_res[c];
     }
-    for (int c = tid; c < N; c += kRtThreads) sbias[c] = a.bias ? a.bias[c] : 0.f;
+    for (int c = tid; c < N; c += kRtThreads) {
+        sbias[c] = a.bias ? a.bias[c] : 0.f;
+        s_hist[c] = 0;
+    }
     __syncthreads();
 
     // logits, all threads: element c -> (token c / rows, row c % rows)
@@ -250,37 +256,62 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
     }
     __syncthreads();
 
-    if (tid < n_tok) {
-        const float *Lr = dots + tid * DSTR;
+    // Softmax, Top-K, a1: threads 4 tok .. 4 tok + 3 share token tok; thread q owns
+    // the experts i = q, q + 4, ...  (every thread runs this, so the shuffles are
+    // whole; tokens past the end compute on a copy of the last token and store nothing)
+    {
+        const int tok = tid >> 2, q = tid & 3;
+        const bool valid = tok < n_tok;
+        const float *Lr = dots + tok * DSTR;
         float mx = -INFINITY;
-        for (int i = 0; i < N; ++i) mx = fmaxf(mx, Lr[i]);
+        for (int i = q; i < N; i += 4) mx = fmaxf(mx, Lr[i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 1, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, 2, kWave));
         float sum = 0.f;
-        for (int i = 0; i < N; ++i) sum += __expf(Lr[i] - mx);
+        for (int i = q; i < N; i += 4) sum += __expf(Lr[i] - mx);
+        sum += __shfl_xor(sum, 1, kWave);
+        sum += __shfl_xor(sum, 2, kWave);
         const float inv = 1.f / sum;
-        unsigned long long taken = 0ull;
-        const size_t t = (size_t)(t0 + tid);
+        unsigned long long taken = 0ull;            // of this thread's own experts
+        const size_t t = (size_t)(t0 + tok);
         for (int s = 0; s < K; ++s) {
             float bv = -INFINITY;
-            int bi = 0;
-            bool have = false;
-            for (int i = 0; i < N; ++i) {
+            int bi = 0x7fffffff;                    // none yet
+            for (int i = q; i < N; i += 4) {
                 const float v = Lr[i];
-                if (!((taken >> i) & 1ull) && (!have || v > bv)) {
+                if (!((taken >> i) & 1ull) && (bi == 0x7fffffff || v > bv)) {
                     bv = v;
                     bi = i;
-                    have = true;
                 }
             }
-            taken |= 1ull << bi;
-            a.topk_idx[t * K + s] = bi;
-            a.topk_w[t * K + s] = __expf(bv - mx) * inv;
+#pragma unroll
+            for (int o = 1; o <= 2; o <<= 1) {
+                const float ov = __shfl_xor(bv, o, kWave);
+                const int oi = __shfl_xor(bi, o, kWave);
+                // larger logit wins, equal logits go to the lower index
+                if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) {
+                    bv = ov;
+                    bi = oi;
+                }
+            }
+            if ((bi & 3) == q) taken |= 1ull << bi;
+            if (valid && q == 0) {
+                a.topk_idx[t * K + s] = bi;
+                a.topk_w[t * K + s] = __expf(bv - mx) * inv;
+                if (a.chunk_hist) atomicAdd(&s_hist[bi], 1);   // integer counts: the same on every run
+            }
         }
-        for (int j = 0; j < nc; ++j)
-            a.alpha1[t * nc + j] = 1.f / (1.f + expf(Lr[N + 2 * j + 1] - Lr[N + 2 * j]));
+        if (valid)
+            for (int j = q; j < nc; j += 4)
+                a.alpha1[t * nc + j] = 1.f / (1.f + expf(Lr[N + 2 * j + 1] - Lr[N + 2 * j]));
     }
     // out_gate block [n_tok, N] is contiguous in memory: coalesced copy from LDS
     for (int c = tid; c < n_tok * N; c += kRtThreads)
         a.out_gate[(size_t)t0 * N + c] = dots[(c / N) * DSTR + c % N];
+    if (a.chunk_hist) {
+        __syncthreads();
+        for (int c = tid; c < N; c += kRtThreads) a.chunk_hist[(size_t)blockIdx.x * N + c] = s_hist[c];
+    }
 }
 
 bool router_mfma_supported(const Dims &d) {
@@ -288,25 +319,32 @@ bool router_mfma_supported(const Dims &d) {
     return d.D % (2 * kRtBK) == 0 && d.N + 2 * d.n_const <= 64;
 }
 
+// Tokens per workgroup of the kernel launch_router_mfma picks for these sizes
+// (also the tokens per chunk of the histogram it leaves for the permutation).
+int router_mfma_block_tokens(const Dims &d) {
+    const int rows = d.N + 2 * d.n_const;
+    const int KT = d.D / kRtBK;
+    // 128-token workgroups read the weight tiles half as often; 64-token ones
+    // fill the chip sooner when there are few tokens
+    return rows <= 32 && KT % 8 == 0 && d.T >= 24576 ? 128 : 64;
+}
+
 hipError_t launch_router_mfma(const RouterArgs &a, hipStream_t s) {
     if (a.d.T == 0) return hipSuccess;
     const int rows = a.d.N + 2 * a.d.n_const;
     const int nblk = (rows + 31) / 32;
-    const int n4 = nblk * 32 * (a.d.D / 4);
-    hipLaunchKernelGGL(k_router_split, dim3((n4 + 255) / 256), dim3(256), 0, s, a, nblk);
     const int KT = a.d.D / kRtBK;
-    auto grid = [&](int tok) { return dim3((a.d.T + tok - 1) / tok); };
+    const int tok = router_mfma_block_tokens(a.d);
+    const dim3 grid((a.d.T + tok - 1) / tok);
     if (nblk == 1) {
-        // 128-token workgroups read the weight tiles half as often; 64-token ones
-        // fill the chip sooner when there are few tokens
-        if (KT % 8 == 0 && a.d.T >= 24576)
-            hipLaunchKernelGGL((k_router_mfma<1, 8, 128, 2>), grid(128), dim3(512), 0, s, a);
+        if (tok == 128)
+            hipLaunchKernelGGL((k_router_mfma<1, 4, 128, 2>), grid, dim3(512), 0, s, a);
         else if (KT % 4 == 0)
-            hipLaunchKernelGGL((k_router_mfma<1, 4, 64, 3>), grid(64), dim3(256), 0, s, a);
+            hipLaunchKernelGGL((k_router_mfma<1, 4, 64, 3>), grid, dim3(256), 0, s, a);
         else
-            hipLaunchKernelGGL((k_router_mfma<1, 2, 64, 3>), grid(64), dim3(256), 0, s, a);
+            hipLaunchKernelGGL((k_router_mfma<1, 2, 64, 3>), grid, dim3(256), 0, s, a);
     } else {
-        hipLaunchKernelGGL((k_router_mfma<2, 2, 64, 2>), grid(64), dim3(256), 0, s, a);
+        hipLaunchKernelGGL((k_router_mfma<2, 2, 64, 2>), grid, dim3(256), 0, s, a);
     }
     return hipGetLastError();
 }

@@ -298,8 +298,62 @@ def test_step_calls_equal_the_fused_call_and_timing_reports():
                     dev["const_vecs"], dev["W_c"])
     ms = L.get_timing()
     say("kernel ms", ms)
-    assert all(v > 0 for k, v in ms.items() if k != "balance") and ms["balance"] == 0   # statistics are off
+    # the router kernel counts its own selections and the scatter kernel scans: no
+    # histogram or scan kernel of their own at this size; the statistics are off
+    assert all(v > 0 for k, v in ms.items() if k not in ("balance", "perm_hist", "perm_scan"))
+    assert ms["balance"] == 0 and ms["perm_hist"] == 0 and ms["perm_scan"] == 0
+    L.set_variant(1)                                  # the generic router leaves no histogram
+    L.layer_forward(dev["x"], dev["prev_gate"], dev["W_g"], dev["W_res"], packed,
+                    dev["const_vecs"], dev["W_c"])
+    ms = L.get_timing()
+    assert ms["perm_hist"] > 0 and ms["perm_scatter"] > 0
     L.set_timing(False)
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+def test_more_chunks_than_one_scatter_kernel_scans_itself(variant):
+    """So many slots that the permutation falls back to a scan kernel of its own
+    (more than 2048 chunks), with capacities on; with the MFMA router the chunks
+    are the router's 64-token workgroups, with the generic one 256 slots."""
+    s = small_shape("manychunks", T=270000, D=128, F=64, n_ffn=5, seed=151)
+    inp = make_inputs(s)
+    L = make_layer(s)
+    cap = L.capacity(s.T, 1.1, 0.75)
+    res = gpu_forward(s, inp, variant=variant, layer=L, cap=cap, intermediates=False)
+    toks = sample_tokens(s, res["topk_idx"], 2048, seed=3)
+    say("many chunks", check_layer(s, inp, res, tok_list=toks, cap=np.array(cap, np.int32), check_inter=False))
+
+
+def test_step_calls_in_any_mix_leave_the_same_permutation():
+    """moepp_permute after moepp_route (the router's own histogram), a second
+    moepp_permute without a new route (its own histogram pass), and with other
+    capacities in between: the tables are always those of the oracle."""
+    import torch
+    s = small_shape("mix", T=6000, D=256, F=128, n_ffn=6, seed=161)
+    inp = make_inputs(s)
+    dev = to_device(s, inp)
+    L = make_layer(s)
+    L.set_variant(2)
+    ref = oracle.permute(s, oracle.route(s, inp["x"], inp["prev_gate"], inp["W_g"], inp["W_res"])["topk_idx"])
+    L.route(dev["x"], dev["prev_gate"], dev["W_g"], dev["W_res"], dev["W_c"])
+    for rep in range(3):
+        if rep == 1:
+            L.set_capacity([7] * s.N)
+        if rep == 2:
+            L.set_capacity(None)
+        L.permute()
+        torch.cuda.synchronize()
+        r = {k: v.cpu().numpy() for k, v in L.get_routing().items()}
+        if rep == 1:
+            assert r["offsets"][-1] == 7 * s.n_ffn and (r["row_of"] == -2).sum() > 0
+            continue
+        if not np.array_equal(r["topk_idx"], oracle.route(s, inp["x"], inp["prev_gate"], inp["W_g"],
+                                                           inp["W_res"])["topk_idx"]):
+            pytest.skip("a near-tie token in this seed")
+        for k in ("counts", "offsets", "row_of"):
+            assert np.array_equal(r[k], ref[k]), (rep, k)
+        R = int(ref["offsets"][-1])
+        assert np.array_equal(r["src_of"][:R], ref["src_of"][:R]), rep
 
 
 def test_mfma_and_generic_kernels_agree():
