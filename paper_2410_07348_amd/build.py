@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoepp.so")
 SOURCES = ["moepp_api.hip", "router_generic.hip", "router_mfma.hip", "permute.hip",
-           "ffn_generic.hip", "ffn_mfma.hip", "combine.hip", "calib.hip"]
+           "ffn_generic.hip", "ffn_mfma.hip", "ffn_decode.hip", "combine.hip", "calib.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed fp32 VALU forms are not to be generated on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -166,6 +166,10 @@ hipError_t launch_ffn_generic(const FfnArgs &a, bool bf16, int which, hipStream_
 bool ffn_mfma_supported(const Dims &d);
 hipError_t launch_ffn_mfma(const FfnArgs &a, int which, hipStream_t s);
 
+// few rows per expert (T * k <= 16 n_ffn): weight-streaming kernels
+bool ffn_decode_supported(const Dims &d);
+hipError_t launch_ffn_decode(const FfnArgs &a, int which, hipStream_t s);
+
 hipError_t launch_combine(const CombineArgs &a, bool bf16, hipStream_t s);
 
 hipError_t launch_pack(const Dims &d, bool bf16, const void *w1, const void *w3,

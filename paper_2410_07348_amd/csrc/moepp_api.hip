@@ -273,15 +273,18 @@ moepp_status do_ffn(moepp_ctx *c, hipStream_t s, int T, const void *x, const voi
     a.h_rows = c->desc.T_max * c->desc.k;
     a.no_tail = c->variant == 3;
     const bool bf = c->desc.act == MOEPP_BF16;
+    // a handful of rows per expert: the kernels that only stream the weights
+    // (variant 3 keeps the tiled kernels, so that tests can compare the two)
+    const bool decode = mfma && c->variant != 3 && ffn_decode_supported(a.d);
     hipError_t e;
     {
         KernelTimer kt(c, s, MOEPP_K_GEMM1);
-        e = mfma ? launch_ffn_mfma(a, 0, s) : launch_ffn_generic(a, bf, 0, s);
+        e = decode ? launch_ffn_decode(a, 0, s) : mfma ? launch_ffn_mfma(a, 0, s) : launch_ffn_generic(a, bf, 0, s);
     }
     if (e != hipSuccess) return MOEPP_EHIP;
     {
         KernelTimer kt(c, s, MOEPP_K_GEMM2);
-        e = mfma ? launch_ffn_mfma(a, 1, s) : launch_ffn_generic(a, bf, 1, s);
+        e = decode ? launch_ffn_decode(a, 1, s) : mfma ? launch_ffn_mfma(a, 1, s) : launch_ffn_generic(a, bf, 1, s);
     }
     return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
 }

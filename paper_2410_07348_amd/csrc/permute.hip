@@ -115,13 +115,30 @@ __global__ __launch_bounds__(kScanWaves *kWave) void k_perm_scan(Dims d, Workspa
 // expert e (both LDS, read only).  A slot's rank is rank[e] plus the number of
 // lower lanes on the same expert; the lowest lane of the group then moves
 // rank[e] past the group.
+constexpr int kPermMaxRounds = 16;     // a chunk has at most 1024 slots (128 tokens x 8)
+
+// The experts of this lane's slots of chunk c, one per round of 64 slots (-1: no
+// slot): all loads are issued here, before anything waits for one.
+__device__ inline void chunk_experts(const Dims &d, const Workspace &w, int c, int chunk_slots, int lane,
+                                     int (&ex)[kPermMaxRounds]) {
+    const int end = min(d.T * d.k, (c + 1) * chunk_slots);
+#pragma unroll
+    for (int it = 0; it < kPermMaxRounds; ++it) {
+        const int q = c * chunk_slots + it * kWave + lane;
+        ex[it] = it * kWave < chunk_slots ? slot_expert(w.topk_idx, q, end, d.N) : -1;
+    }
+}
+
 __device__ inline void scatter_chunk(const Dims &d, const Workspace &w, int c, int chunk_slots, int lane,
-                                     volatile int *rank, const int *first_row, const int *limit) {
+                                     const int (&ex)[kPermMaxRounds], volatile int *rank,
+                                     const int *first_row, const int *limit) {
     const int total = min(d.T * d.k, (c + 1) * chunk_slots);     // end of this chunk
     const unsigned long long lt = (1ull << lane) - 1ull;
-    for (int q0 = c * chunk_slots; q0 < total; q0 += kWave) {
-        const int q = q0 + lane;
-        const int e = slot_expert(w.topk_idx, q, total, d.N);
+#pragma unroll
+    for (int it = 0; it < kPermMaxRounds; ++it) {
+        if (it * kWave >= chunk_slots) break;
+        const int q = c * chunk_slots + it * kWave + lane;
+        const int e = ex[it];
         const unsigned long long m = same_expert_lanes(e);
         if (e >= 0) {
             const int old = rank[e];
@@ -149,9 +166,13 @@ __global__ __launch_bounds__(kPermWaves *kWave) void k_perm_scatter(Dims d, Work
         s_first[lane] = lane < d.n_ffn ? w.offsets[lane] : 0;
         s_limit[lane] = cap.on && lane < d.N ? cap.cap[lane] : 0x7fffffff;
     }
-    if (active) s_rank[wv][lane] = lane < d.N ? w.chunk_base[c * d.N + lane] : 0;
+    int ex[kPermMaxRounds];
+    if (active) {
+        chunk_experts(d, w, c, chunk_slots, lane, ex);
+        s_rank[wv][lane] = lane < d.N ? w.chunk_base[c * d.N + lane] : 0;
+    }
     __syncthreads();
-    if (active) scatter_chunk(d, w, c, chunk_slots, lane, s_rank[wv], s_first, s_limit);
+    if (active) scatter_chunk(d, w, c, chunk_slots, lane, ex, s_rank[wv], s_first, s_limit);
 }
 
 // Scan and scatter in one kernel, for at most kPermDirectChunks chunks.  Every
@@ -176,6 +197,8 @@ __global__ __launch_bounds__(kPermWaves *kWave) void k_perm_scan_scatter(Dims d,
     while (NP < N) NP <<= 1;
     const int per = kWave / NP;                    // rows a wave adds per step
     const int e = lane % NP, sub = lane / NP;
+    int ex[kPermMaxRounds];                        // this chunk's slots: in flight while the table is added up
+    if (c < n_chunks) chunk_experts(d, w, c, chunk_slots, lane, ex);
     const int tile_rows = kScanTileInts / N;       // whole rows per piece (N <= 64: at least 128)
     const int total_ints = n_chunks * N;           // <= kPermDirectChunks * 64
     int before = 0, all = 0;
@@ -248,7 +271,7 @@ __global__ __launch_bounds__(kPermWaves *kWave) void k_perm_scan_scatter(Dims d,
     // fence keeps the compiler from moving the reads below above these writes)
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    scatter_chunk(d, w, c, chunk_slots, lane, s_rank[wv], s_first[wv], s_limit[wv]);
+    scatter_chunk(d, w, c, chunk_slots, lane, ex, s_rank[wv], s_first[wv], s_limit[wv]);
 }
 
 // The three steps in one workgroup, for calls with at most kPermSmallSlots
@@ -287,7 +310,11 @@ __global__ __launch_bounds__(kPermSmallWaves *kWave) void k_perm_small(Dims d, W
         if (lane == 0) w.offsets[0] = 0;
     }
     __syncthreads();
-    if (c * kPermChunk < total) scatter_chunk(d, w, c, kPermChunk, lane, s_rank[c], s_first, s_limit);
+    if (c * kPermChunk < total) {
+        int ex[kPermMaxRounds];
+        chunk_experts(d, w, c, kPermChunk, lane, ex);
+        scatter_chunk(d, w, c, kPermChunk, lane, ex, s_rank[c], s_first, s_limit);
+    }
 }
 
 // ---- load-balance statistics (Eq.7) ---------------------------------------
@@ -356,6 +383,7 @@ hipError_t launch_perm_scan(const Dims &d, const Workspace &w, const CapArgs &ca
 hipError_t launch_perm_scatter(const Dims &d, const Workspace &w, const CapArgs &cap, int chunk_slots,
                                hipStream_t s) {
     if (d.T == 0) return hipSuccess;
+    if (chunk_slots > kPermMaxRounds * kWave) return hipErrorInvalidValue;
     const dim3 grid(perm_blocks(perm_chunks(d, chunk_slots))), block(kPermWaves * kWave);
     hipLaunchKernelGGL(k_perm_scatter, grid, block, 0, s, d, w, cap, chunk_slots);
     return hipGetLastError();
@@ -364,7 +392,7 @@ hipError_t launch_perm_scan_scatter(const Dims &d, const Workspace &w, const Cap
                                     hipStream_t s) {
     if (d.T == 0) return hipSuccess;
     const int n_chunks = perm_chunks(d, chunk_slots);
-    if (n_chunks > kPermDirectChunks) return hipErrorInvalidValue;
+    if (n_chunks > kPermDirectChunks || chunk_slots > kPermMaxRounds * kWave) return hipErrorInvalidValue;
     const dim3 grid(perm_blocks(n_chunks)), block(kPermWaves * kWave);
     hipLaunchKernelGGL(k_perm_scan_scatter, grid, block, 0, s, d, w, cap, chunk_slots, n_chunks);
     return hipGetLastError();

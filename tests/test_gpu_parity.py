@@ -356,6 +356,48 @@ def test_step_calls_in_any_mix_leave_the_same_permutation():
         assert np.array_equal(r["src_of"][:R], ref["src_of"][:R]), rep
 
 
+@pytest.mark.parametrize("kw", [
+    dict(T=40, D=512, F=768, n_ffn=6, seed=171),          # K = 512 / 768: 2 and 3 steps per wave
+    dict(T=64, D=1024, F=256, n_ffn=8, seed=172),
+    dict(T=7, D=256, F=512, n_ffn=3, k=3, seed=173),
+    dict(T=30, D=1280, F=1536, n_ffn=4, seed=174),        # 5 and 6 steps per wave
+])
+def test_few_rows_per_expert_take_the_weight_streaming_kernels(kw):
+    """T * k <= 16 n_ffn: the FFN runs in the kernels that only stream the expert
+    weights.  Checked against the oracle, and against the tiled kernels (variant 3)."""
+    s = small_shape("decode", **kw)
+    assert s.T * s.k <= 16 * s.n_ffn and s.D % 256 == 0 and s.F % 256 == 0
+    inp = make_inputs(s)
+    say("decode", kw)
+    a = gpu_forward(s, inp, variant=2)
+    say("errs", check_layer(s, inp, a))
+    b = gpu_forward(s, inp, variant=3)
+    assert np.array_equal(a["topk_idx"], b["topk_idx"]) and np.array_equal(a["row_of"], b["row_of"])
+    assert rel_err(a["h"], b["h"]) <= 1e-2 and rel_err(a["out"], b["out"]) <= 1e-2
+
+
+def test_weight_streaming_kernels_with_long_empty_and_single_row_groups():
+    """Forced routing: one expert takes 37 rows (three blocks of 16, the last with
+    5 rows), one takes none (its weights must not be needed), one takes a single row."""
+    s = small_shape("decode_groups", T=48, D=512, F=512, n_ffn=6, seed=175)
+    nf = s.n_ffn
+    idx = np.empty((s.T, 2), np.int64)
+    idx[:, 0] = np.where(np.arange(s.T) < 37, 1, 3)            # expert 1: 37 rows, expert 3: 11 rows
+    idx[:, 1] = nf + (np.arange(s.T) % (s.N - nf))              # zero-computation experts
+    idx[40, 1] = 4                                              # expert 4: one row; experts 0, 2, 5: none
+    inp = forced_routing(s, idx)
+    # poison the weights of the experts without rows: a kernel that touched them would show it
+    for name in ("w1", "w3", "w2"):
+        for e in (0, 2, 5):
+            inp[name][e] = np.float32(np.nan)
+    res = gpu_forward(s, inp, variant=2)
+    assert np.array_equal(res["topk_idx"], idx)
+    assert res["counts"][:nf].tolist() == [0, 37, 0, 11, 1, 0]
+    assert np.isfinite(res["out"]).all()
+    inp_ok = {k: (np.nan_to_num(v) if k in ("w1", "w3", "w2") else v) for k, v in inp.items()}
+    say("errs", check_layer(s, inp_ok, res, max_near_ties=0))
+
+
 def test_mfma_and_generic_kernels_agree():
     """The two kernel families must give the same routing and close outputs."""
     s = small_shape("families", T=900, D=512, F=768, n_ffn=6)
