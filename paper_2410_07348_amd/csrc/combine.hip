@@ -16,7 +16,9 @@ namespace moepp {
 
 constexpr int kCombineWaves = 4;
 
-template <typename AT>
+// KMAX: slots the kernel is unrolled for (2: the paper's Top-2 layers keep their
+// per-slot plan in a handful of registers; kMaxTopK: any k).
+template <typename AT, int KMAX>
 __global__ __launch_bounds__(kCombineWaves *kWave) void k_combine(CombineArgs a) {
     const int lane = threadIdx.x % kWave;
     const int t = blockIdx.x * kCombineWaves + threadIdx.x / kWave;
@@ -26,12 +28,12 @@ __global__ __launch_bounds__(kCombineWaves *kWave) void k_combine(CombineArgs a)
     constexpr int V = ActVec<AT>::N;
 
     // Per-slot plan (wave-uniform): coefficient of a gathered row, of x, of v_j.
-    float g_row[kMaxTopK], g_x[kMaxTopK], g_v[kMaxTopK];
-    const AT *p_row[kMaxTopK];
-    const AT *p_v[kMaxTopK];
+    float g_row[KMAX], g_x[KMAX], g_v[KMAX];
+    const AT *p_row[KMAX];
+    const AT *p_v[KMAX];
     bool need_x = false;
 #pragma unroll
-    for (int s = 0; s < kMaxTopK; ++s) {
+    for (int s = 0; s < KMAX; ++s) {
         g_row[s] = g_x[s] = g_v[s] = 0.f;
         p_row[s] = p_v[s] = nullptr;
         if (s < K) {
@@ -60,7 +62,7 @@ __global__ __launch_bounds__(kCombineWaves *kWave) void k_combine(CombineArgs a)
     }
     const AT *xt = static_cast<const AT *>(a.x) + (size_t)t * D;
     AT *ot = static_cast<AT *>(a.out) + (size_t)t * D;
-#pragma unroll 2
+#pragma unroll 4
     for (int d = lane * V; d < D; d += kWave * V) {
         float acc[V];
 #pragma unroll
@@ -68,7 +70,7 @@ __global__ __launch_bounds__(kCombineWaves *kWave) void k_combine(CombineArgs a)
         ActVec<AT> xv;
         if (need_x) xv = load_vec_stream(xt + d);
 #pragma unroll
-        for (int s = 0; s < kMaxTopK; ++s) {
+        for (int s = 0; s < KMAX; ++s) {
             if (s < K) {
                 if (p_row[s]) {
                     ActVec<AT> rv = load_vec_stream(p_row[s] + d);   // read once
@@ -95,8 +97,13 @@ __global__ __launch_bounds__(kCombineWaves *kWave) void k_combine(CombineArgs a)
 hipError_t launch_combine(const CombineArgs &a, bool bf16, hipStream_t s) {
     if (a.d.T == 0) return hipSuccess;
     dim3 grid((a.d.T + kCombineWaves - 1) / kCombineWaves), block(kCombineWaves * kWave);
-    if (bf16) hipLaunchKernelGGL(k_combine<bf16_t>, grid, block, 0, s, a);
-    else hipLaunchKernelGGL(k_combine<float>, grid, block, 0, s, a);
+    if (a.d.k <= 2) {
+        if (bf16) hipLaunchKernelGGL((k_combine<bf16_t, 2>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_combine<float, 2>), grid, block, 0, s, a);
+    } else {
+        if (bf16) hipLaunchKernelGGL((k_combine<bf16_t, kMaxTopK>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_combine<float, kMaxTopK>), grid, block, 0, s, a);
+    }
     return hipGetLastError();
 }
 
