@@ -177,6 +177,10 @@ __global__ __launch_bounds__(G::NT, 1) void k_grouped_gemm(GemmArgs a) {
     // x + 8*(j % jstride), jstride = workgroups per XCD (persistent kernel) or
     // by workgroup x + 8*j (one tile per workgroup).  The order is computed
     // here from the group offsets.
+    // Assumes the part this library is written for, MI355X in its default (SPX)
+    // partition mode: 8 XCDs of 32 CUs, workgroup w dispatched to XCD w % 8.  On
+    // another partitioning the tile order is still a valid enumeration (every tile
+    // is computed once), only the sharing in L2 it is built for is lost.
     constexpr int GM = 8, GN = 4, NXCD = 8;
     const int Nt = a.n_ntiles;
     // Lane q holds group q: one vector load of the offsets, a wave-wide prefix
