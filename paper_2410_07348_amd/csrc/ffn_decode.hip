@@ -9,10 +9,12 @@
 // against a few MB of activations), so it is built around that stream:
 //  * an expert without rows is never touched: zero-computation slots and
 //    unselected experts remove whole weight reads here (paper Sec. 3.4);
-//  * work unit = (expert, block of 16 of its rows, group of 64 weight rows); the
-//    units of all experts form one list in that order and every workgroup takes a
-//    consecutive piece of it, so a workgroup stays with one expert (and one set of
-//    token operands) as long as it can;
+//  * work unit = (expert, block of 16 of its rows, panel of 256 packed weight
+//    rows); the units of all experts form one list in that order, every four
+//    neighbouring workgroups take a consecutive piece of it and each of the four
+//    works on one of the panel's four groups of 64 rows, so a workgroup stays with
+//    one expert (and one set of token operands) as long as it can, and what the
+//    four read at about the same time is consecutive memory;
 //  * the eight waves of a workgroup split the reduction over K: wave w owns K
 //    steps [S w, S (w + 1)) of 32 and keeps its slice of the (at most 16) token
 //    rows in registers as MFMA operands for as long as the row block stays the
@@ -66,13 +68,17 @@ __global__ __launch_bounds__(kDecThreads, 1) void k_ffn_decode(DecodeArgs a) {
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int l16 = lane % 16, lq = lane / 16;
-    const int upe = a.Nb / 64;                     // groups of 64 weight rows per expert
+    const int ppe = (a.Nb + kPanel - 1) / kPanel;  // panels of 256 packed weight rows per expert
+    // Four neighbouring workgroups share a list of (expert, row block, panel) and each takes one
+    // of the panel's four groups of 64 rows: what they read at about the same time is the 16 KB
+    // of consecutive memory of one K slab of the panel, not four pieces from four places.
+    const int sub = blockIdx.x % 4, quad = blockIdx.x / 4, n_quads = gridDim.x / 4;
 
     // ---- the unit list: lane q looks after expert q --------------------------
     const int eq = lane < a.n_ffn ? lane : a.n_ffn;
     const int o_lo = a.offsets[eq];
     const int o_hi = a.offsets[eq < a.n_ffn ? eq + 1 : eq];
-    const int units_q = ((o_hi - o_lo + 15) / 16) * upe;      // 0 for an expert without rows
+    const int units_q = ((o_hi - o_lo + 15) / 16) * ppe;      // 0 for an expert without rows
     int incl = units_q;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
@@ -80,13 +86,14 @@ __global__ __launch_bounds__(kDecThreads, 1) void k_ffn_decode(DecodeArgs a) {
         if (lane >= d) incl += up;
     }
     const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
-    const int u0 = (int)((long long)total * blockIdx.x / gridDim.x);
-    const int u1 = (int)((long long)total * (blockIdx.x + 1) / gridDim.x);
+    const int u0 = (int)((long long)total * quad / n_quads);
+    const int u1 = (int)((long long)total * (quad + 1) / n_quads);
     if (u0 >= u1) return;
 
-    // unit u -> expert, first row of its row block, rows in it, weight-row group
+    // unit u -> expert, first row of its row block, rows in it, weight-row group, panel
+    // (nrows = 0: the panel has no group for this workgroup; a valid one is computed, nothing stored)
     struct Unit {
-        int e, row0, nrows, g;
+        int e, row0, nrows, g, panel;
     };
     auto locate = [&](int u) {
         const unsigned long long past = __ballot(incl > u);
@@ -94,10 +101,15 @@ __global__ __launch_bounds__(kDecThreads, 1) void k_ffn_decode(DecodeArgs a) {
         r.e = __builtin_ctzll(past);
         const int local = u - __builtin_amdgcn_readlane(incl - units_q, r.e);
         const int lo = __builtin_amdgcn_readlane(o_lo, r.e), hi = __builtin_amdgcn_readlane(o_hi, r.e);
-        const int rb = local / upe;                            // row blocks outermost: the token operands stay
-        r.g = local - rb * upe;
+        const int rb = local / ppe;                            // row blocks outermost: the token operands stay
+        r.panel = local - rb * ppe;
+        r.g = r.panel * 4 + sub;
         r.row0 = lo + 16 * rb;
         r.nrows = hi - r.row0 < 16 ? hi - r.row0 : 16;
+        if (r.g * 64 >= a.Nb) {                                // a last panel with fewer than four groups
+            r.g = a.Nb / 64 - 1;
+            r.nrows = 0;
+        }
         return r;
     };
 
@@ -123,7 +135,8 @@ __global__ __launch_bounds__(kDecThreads, 1) void k_ffn_decode(DecodeArgs a) {
     bf16x8 af[S];
     auto load_tokens = [&](const Unit &un) {
         int row = un.row0 + l16;
-        row = row < un.row0 + un.nrows ? row : un.row0 + un.nrows - 1;
+        const int last = un.row0 + (un.nrows > 0 ? un.nrows - 1 : 0);
+        row = row < last ? row : last;
         const char *p;
         size_t step;
         if constexpr (SWIGLU) {
@@ -197,7 +210,7 @@ __global__ __launch_bounds__(kDecThreads, 1) void k_ffn_decode(DecodeArgs a) {
     int u = u0;
     while (u < u1) {
         Unit cur = locate(u);
-        const int seg_end = min(u1, u + (upe - cur.g));        // units that share cur's token operands
+        const int seg_end = min(u1, u + (ppe - cur.panel));    // units that share cur's token operands
         load_tokens(cur);
 #pragma unroll
         for (int r = 0; r < kDecRing; ++r)
@@ -279,9 +292,9 @@ hipError_t launch_ffn_decode(const FfnArgs &f, int which, hipStream_t s) {
     if (n_cu == 0) {
         int dev = 0, v = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 4)
             v = 256;
-        n_cu = v;
+        n_cu = v / 4 * 4;             // workgroups come in fours (one panel each)
     }
     // one workgroup per CU; a workgroup without units returns at once
     const int S = a.K / (32 * kDecWaves);
