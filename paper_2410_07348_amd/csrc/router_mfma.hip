@@ -79,9 +79,8 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
     const int KT = D / kRtBK;                             // a multiple of PF (the launcher checks)
 
     // ---- tile loads ------------------------------------------------------------
-    // x chunk c = tid + 512 i (i = 0, 1): tile row c / 8, LDS slot c % 8 holds
+    // x chunk c = tid + threads i (i = 0, 1): tile row c / 8, LDS slot c % 8 holds
     // global chunk slot ^ swz(row), so the LDS position of chunk c is simply 16 c.
-    // Weight chunk tid + 512 i: plain copy of the pre-split buffer.
     const char *px[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -189,6 +188,24 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
     for (int p = 0; p < PF; ++p) load_regs(p, xr[p], wr[p]);
     store_regs(lds, xr[0], wr[0]);
     load_regs(PF, xr[0], wr[0]);
+    // The epilogue's own operands (this block's previous-layer logits, W_g of the
+    // gating residual, the bias) are asked for now and wait in registers: loaded
+    // after the loop, their latency would sit on every workgroup's critical path.
+    const int n_tok = min(kRtTok, T - t0);
+    constexpr int PGN = ROWS / 4;                                      // >= N / 4
+    constexpr int WRN = (ROWS * ROWS + kRtThreads - 1) / kRtThreads;   // >= N N / threads
+    float pg[PGN], wg[WRN], bs = 0.f;
+#pragma unroll
+    for (int i = 0; i < PGN; ++i) {
+        const int c = tid + kRtThreads * i;
+        pg[i] = a.prev_gate && c < n_tok * N ? a.prev_gate[(size_t)t0 * N + c] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < WRN; ++i) {
+        const int c = tid + kRtThreads * i;
+        wg[i] = a.prev_gate && c < N * N ? a.W_res[c] : 0.f;
+    }
+    if (a.bias && tid < N) bs = a.bias[tid];
     lds_barrier();
     for (int kt0 = 0; kt0 < KT; kt0 += PF) {
 #pragma unroll
@@ -221,15 +238,21 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
                 dst[(tb * 32 + l32) * DSTR + b * 32 + 8 * (v / 4) + 4 * lh + (v % 4)] =
                     acc_hi[b][v] + acc_lo[b][v];
     }
-    const int n_tok = min(kRtTok, T - t0);
     if (a.prev_gate) {
-        for (int c = tid; c < n_tok * N; c += kRtThreads)
-            prevs[(c / N) * (N + 1) + c % N] = a.prev_gate[(size_t)t0 * N + c];
-        for (int c = tid; c < N * N; c += kRtThreads) wres[c] = a.W_res[c];
+#pragma unroll
+        for (int i = 0; i < PGN; ++i) {
+            const int c = tid + kRtThreads * i;
+            if (c < n_tok * N) prevs[(c / N) * (N + 1) + c % N] = pg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < WRN; ++i) {
+            const int c = tid + kRtThreads * i;
+            if (c < N * N) wres[c] = wg[i];
+        }
     }
-    for (int c = tid; c < N; c += kRtThreads) {
-        sbias[c] = a.bias ? a.bias[c] : 0.f;
-        s_hist[c] = 0;
+    if (tid < N) {                 // N <= 64 < threads
+        sbias[tid] = bs;
+        s_hist[tid] = 0;
     }
     __syncthreads();
 
