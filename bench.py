@@ -386,6 +386,7 @@ def main():
             o = {"T": so.T, "D": so.D, "F": so.F, "ffn_rows_R": go["R"],
                  "ms_per_step": go["ms_per_step"], "ms_per_step_no_events": go["ms_per_step_no_events"],
                  "tokens_per_s": so.T / (go["ms_per_step"] * 1e-3),
+                 "tokens_per_s_no_events": so.T / (go["ms_per_step_no_events"] * 1e-3),
                  "expert_forward_tokens_per_s": so.T / (eo * 1e-3), "kernel_ms": ko,
                  "pct_bf16_mfma_peak_ffn": 100.0 * ro.get("ffn_tflops", 0.0) / PEAK_BF16_MFMA_TFLOPS,
                  "gemm1_tflops": ro.get("gemm1_tflops"), "gemm2_tflops": ro.get("gemm2_tflops"),
