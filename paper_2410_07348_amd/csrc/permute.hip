@@ -214,6 +214,7 @@ __global__ __launch_bounds__(kPermWaves *kWave) void k_perm_scan_scatter(Dims d,
 #pragma unroll
             for (int u = 0; u < PER; ++u) {
                 const int i = (threadIdx.x + u * kPermWaves * kWave) * 4;
+                v[u] = make_int4(0, 0, 0, 0);      // (every element defined: the array stays in registers)
                 if (i < n_ints) v[u] = *reinterpret_cast<const int4 *>(&w.chunk_hist[base + i]);
             }
 #pragma unroll
