@@ -180,27 +180,38 @@ __global__ __launch_bounds__(kPermWaves *kWave) void k_perm_scatter(Dims d, Work
 // its chunk starts at) and in all chunks (the counts, from which it derives kept
 // and the first row of every FFN expert like the scan kernel does).  The
 // workgroup passes the whole table chunk_hist through LDS in pieces of
-// kScanTileInts integers with coalesced 16-byte loads, and its waves add up
-// what they need from there: lane l looks after expert l % NP of rows l / NP,
-// l / NP + 64 / NP, ... of a piece (NP = N rounded up to a power of two).  The
-// wave of chunk 0 also writes counts, kept and offsets.
+// kScanTileInts integers with coalesced 16-byte loads, and its threads share
+// the additions: thread i looks after expert i % NP of the rows i / NP,
+// i / NP + 256 / NP, ... of a piece (NP = N rounded up to a power of two) and
+// adds up all of them and those before the workgroup's first chunk; the partial
+// sums meet in LDS, and a wave adds the rows of the workgroup's chunks before
+// its own.  The wave of chunk 0 also writes counts, kept and offsets.
 constexpr int kScanTileInts = 8192;               // 32 KB of LDS
 __global__ __launch_bounds__(kPermWaves *kWave) void k_perm_scan_scatter(Dims d, Workspace w, CapArgs cap,
                                                                         int chunk_slots, int n_chunks) {
+    constexpr int NT = kPermWaves * kWave;
     __shared__ __attribute__((aligned(16))) int s_tab[kScanTileInts];
+    __shared__ int s_all[NT], s_before[NT];        // [row group][expert slot]: NT / NP groups of NP
     __shared__ int s_rank[kPermWaves][kMaxExperts];
     __shared__ int s_first[kPermWaves][kMaxExperts], s_limit[kPermWaves][kMaxExperts];
     const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
-    const int c = blockIdx.x * kPermWaves + wv;    // may be past the last chunk: such a wave only helps loading
+    const int c0 = blockIdx.x * kPermWaves;        // first chunk of the workgroup
+    const int c = c0 + wv;                         // may be past the last chunk: such a wave only helps adding
     const int N = d.N;
-    int NP = 1;
-    while (NP < N) NP <<= 1;
-    const int per = kWave / NP;                    // rows a wave adds per step
-    const int e = lane % NP, sub = lane / NP;
+    int NP = 1, lg = 0;
+    while (NP < N) NP <<= 1, ++lg;
+    const int e = threadIdx.x & (NP - 1), grp = threadIdx.x >> lg, ngrp = NT >> lg;   // >= 4 row groups
     int ex[kPermMaxRounds];                        // this chunk's slots: in flight while the table is added up
     if (c < n_chunks) chunk_experts(d, w, c, chunk_slots, lane, ex);
+    // the rows of the workgroup's own chunks before this wave's (the table pass stops short of them)
+    int own[kPermWaves - 1];
+#pragma unroll
+    for (int i = 0; i < kPermWaves - 1; ++i)
+        own[i] = i < wv && c0 + i < n_chunks && lane < N ? w.chunk_hist[(c0 + i) * N + lane] : 0;
     const int tile_rows = kScanTileInts / N;       // whole rows per piece (N <= 64: at least 128)
     const int total_ints = n_chunks * N;           // <= kPermDirectChunks * 64
+    // thread (grp, e) adds up expert e over the rows grp, grp + ngrp, ... of every piece:
+    // all of them, and those before the workgroup's first chunk
     int before = 0, all = 0;
     for (int row0 = 0; row0 < n_chunks; row0 += tile_rows) {
         const int base = row0 * N;
@@ -209,45 +220,55 @@ __global__ __launch_bounds__(kPermWaves *kWave) void k_perm_scan_scatter(Dims d,
         // integers; pieces are copied 16 bytes at a time where the alignment allows, else by integers
         if (((base | n_ints) & 3) == 0) {
             // all loads of the piece first, then the LDS writes: one memory latency, not one per load
-            constexpr int PER = kScanTileInts / (kPermWaves * kWave * 4);
+            constexpr int PER = kScanTileInts / (NT * 4);
             int4 v[PER];
 #pragma unroll
             for (int u = 0; u < PER; ++u) {
-                const int i = (threadIdx.x + u * kPermWaves * kWave) * 4;
+                const int i = (threadIdx.x + u * NT) * 4;
                 v[u] = make_int4(0, 0, 0, 0);      // (every element defined: the array stays in registers)
                 if (i < n_ints) v[u] = *reinterpret_cast<const int4 *>(&w.chunk_hist[base + i]);
             }
 #pragma unroll
             for (int u = 0; u < PER; ++u) {
-                const int i = (threadIdx.x + u * kPermWaves * kWave) * 4;
+                const int i = (threadIdx.x + u * NT) * 4;
                 if (i < n_ints) *reinterpret_cast<int4 *>(&s_tab[i]) = v[u];
             }
         } else {
-            for (int i = threadIdx.x; i < n_ints; i += kPermWaves * kWave) s_tab[i] = w.chunk_hist[base + i];
+            for (int i = threadIdx.x; i < n_ints; i += NT) s_tab[i] = w.chunk_hist[base + i];
         }
         __syncthreads();
         const int rows = n_ints / N;
         if (e < N) {
-            constexpr int U = 8;                   // reads in flight: the sums would otherwise wait for each one
-            for (int r0 = sub; r0 < rows; r0 += U * per) {
+            constexpr int U = 4;                   // reads in flight: the sums would otherwise wait for each one
+            for (int r0 = grp; r0 < rows; r0 += U * ngrp) {
                 int v[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) v[u] = r0 + u * per < rows ? s_tab[(r0 + u * per) * N + e] : 0;
+                for (int u = 0; u < U; ++u) v[u] = r0 + u * ngrp < rows ? s_tab[(r0 + u * ngrp) * N + e] : 0;
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     all += v[u];
-                    if (row0 + r0 + u * per < c) before += v[u];
+                    if (row0 + r0 + u * ngrp < c0) before += v[u];
                 }
             }
         }
         __syncthreads();
     }
+    s_all[threadIdx.x] = all;                      // index = grp * NP + e
+    s_before[threadIdx.x] = before;
+    __syncthreads();
     if (c >= n_chunks) return;
-    for (int o = NP; o < kWave; o <<= 1) {         // add the 64 / NP partial sums of an expert
-        before += __shfl_xor(before, o, kWave);
-        all += __shfl_xor(all, o, kWave);
+    // lane l < N: expert l's sums over the row groups (in group order), plus the
+    // workgroup's own chunks before this wave's
+    all = 0;
+    before = 0;
+    if (lane < N) {
+        for (int g = 0; g < ngrp; ++g) {
+            all += s_all[g * NP + lane];
+            before += s_before[g * NP + lane];
+        }
+#pragma unroll
+        for (int i = 0; i < kPermWaves - 1; ++i) before += own[i];
     }
-    // now lanes 0 .. N-1 (and their copies in the other sub-groups) hold expert e's sums
     const int lim = cap.on && lane < N ? cap.cap[lane] : 0x7fffffff;
     const int keep = lane < N ? (lim < all ? lim : all) : 0;
     const int kf = lane < d.n_ffn ? keep : 0;
