@@ -254,7 +254,10 @@ enum {
                             reported as MOEPP_K_SCATTER                       */
     MOEPP_K_SCAN = 2,    /* permute: exclusive scan as a kernel of its own; 0 up to
                             2048 chunks (scan and scatter are one kernel)    */
-    MOEPP_K_SCATTER = 3, /* permute: (scan and) stable scatter                */
+    MOEPP_K_SCATTER = 3, /* permute: (scan and) stable scatter; 0 for calls with at
+                            most 64 tokens on the automatic variant, where the
+                            router's second kernel also groups the slots and the
+                            time is part of MOEPP_K_ROUTER                    */
     MOEPP_K_GEMM1 = 4,   /* grouped GEMM W1/W3 + SwiGLU                       */
     MOEPP_K_GEMM2 = 5,   /* grouped GEMM W2                                   */
     MOEPP_K_COMBINE = 6, /* weighted combine + zero-computation experts       */

@@ -18,6 +18,8 @@ constexpr int kWave = 64;         // CDNA wavefront
 // Calls with at most this many tokens take the router that splits the
 // reduction over D across workgroups.
 constexpr int kRouterSmallT = 256;
+// ... and up to this many its second kernel also does the permutation
+constexpr int kRouterFusedT = 64;
 
 // Permutation: one wave owns a chunk of consecutive slots: kPermChunk of them,
 // or the slots of one workgroup of the MFMA router when that kernel has
@@ -137,8 +139,12 @@ struct CombineArgs {
 // Launchers (each returns hipGetLastError() after its launches).
 // `bf16` selects the activation type; `which` selects GEMM1 / GEMM2.
 hipError_t launch_router_generic(const RouterArgs &a, bool bf16, hipStream_t s);
-// T <= kRouterSmallT only; partial: router_small_bytes() of scratch
-hipError_t launch_router_small(const RouterArgs &a, bool bf16, float *partial, hipStream_t s);
+// T <= kRouterSmallT only; partial: router_small_bytes() of scratch.  With perm_ws
+// (T <= kRouterFusedT only) the second kernel also does the permutation of the
+// call's T*k slots (counts, kept, offsets, row_of, src_of of *perm_ws, capacities
+// *perm_cap), as launch_perm_small would.
+hipError_t launch_router_small(const RouterArgs &a, bool bf16, float *partial, hipStream_t s,
+                               const Workspace *perm_ws = nullptr, const CapArgs *perm_cap = nullptr);
 size_t router_small_bytes();
 bool router_mfma_supported(const Dims &d);
 hipError_t launch_router_mfma(const RouterArgs &a, hipStream_t s);

@@ -24,6 +24,8 @@ struct moepp_ctx {
     const float *last_out_gate;   // logits of the last routed call (read by the statistics)
     int last_T, last_k;
     // the MFMA router leaves a histogram per workgroup for the permutation of the same call
+    bool perm_valid;      // the few-token router kernel has already grouped the slots of call (perm_T, perm_k)
+    int perm_T, perm_k;
     bool hist_valid;
     int hist_T, hist_k, hist_chunk_slots;
     bool timing;
@@ -187,11 +189,18 @@ moepp_status do_route(moepp_ctx *c, hipStream_t s, int T, const void *x, const f
     c->last_k = k;
     c->last_out_gate = out_gate;
     c->hist_valid = false;
+    c->perm_valid = false;
     if (T == 0) return MOEPP_OK;
     KernelTimer kt(c, s, MOEPP_K_ROUTER);
     const bool bf16 = c->desc.act == MOEPP_BF16;
     hipError_t e;
-    if (c->variant == 0 && T <= kRouterSmallT) {
+    if (c->variant == 0 && T <= kRouterFusedT) {
+        // a handful of tokens: the router's second kernel also groups the slots by expert
+        e = launch_router_small(a, bf16, c->ws.router_partial, s, &c->ws, &c->cap);
+        c->perm_valid = e == hipSuccess;
+        c->perm_T = T;
+        c->perm_k = k;
+    } else if (c->variant == 0 && T <= kRouterSmallT) {
         e = launch_router_small(a, bf16, c->ws.router_partial, s);
     } else if (mfma) {
         // the permutation of a call with few slots runs in one workgroup and counts for itself
@@ -213,9 +222,11 @@ moepp_status do_permute(moepp_ctx *c, hipStream_t s, int T, int k) {
     const Dims d = dims_of(c, T, k);
     c->last_T = T;
     c->last_k = k;
-    hipError_t e;
+    hipError_t e = hipSuccess;
     if (T > 0 && T * k <= kPermSmallSlots) {
-        {
+        // (nothing to do when the router kernel of this very call has done it; the
+        // capacities it used are still the current ones, see moepp_set_capacity)
+        if (!(c->perm_valid && c->perm_T == T && c->perm_k == k)) {
             KernelTimer kt(c, s, MOEPP_K_SCATTER);
             e = launch_perm_small(d, c->ws, c->cap, s);
         }
@@ -374,6 +385,7 @@ void init_ctx(moepp_ctx *c, const moepp_desc *desc, void *workspace) {
     c->last_T = 0;
     c->last_k = desc->k;
     c->hist_valid = false;
+    c->perm_valid = false;
     c->hist_T = c->hist_k = c->hist_chunk_slots = 0;
     c->timing = false;
     c->have_events = false;
@@ -494,6 +506,7 @@ moepp_status moepp_capacity(const moepp_desc *desc, int32_t T, int32_t k, double
 
 moepp_status moepp_set_capacity(moepp_ctx *ctx, const int32_t *cap_host) {
     if (!ctx) return MOEPP_EINVAL;
+    ctx->perm_valid = false;      // a permutation done under the old capacities does not stand in for a new one
     if (!cap_host) {
         ctx->cap.on = false;
         return MOEPP_OK;

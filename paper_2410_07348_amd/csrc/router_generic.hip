@@ -7,6 +7,8 @@
 // Top-K runs on the float32 logits; ties go to the lower index and slots are
 // written in descending order of logit.
 #include "common.h"
+#include "perm_device.h"
+#include "router_device.h"
 
 #include <type_traits>
 
@@ -206,11 +208,73 @@ __global__ __launch_bounds__(kRouterWaves *kWave) void k_router_small_final(Rout
     if (active) router_tail(a, t, lane, dots[w], wres);
 }
 
+// The second kernel and the permutation in one launch, for T <= kRouterFusedT: one
+// workgroup adds the slices of every dot product (in slice order), finishes the
+// logits (gating residual, bias) with all threads, does softmax / Top-K / a1 with
+// four threads per token, and then groups the T*k selections, which it still
+// holds in LDS, by expert like k_perm_small does.
+__global__ __launch_bounds__(kPermSmallWaves *kWave) void k_router_small_final_perm(RouterArgs a, int n_splits,
+                                                                                  const float *partial, Workspace w,
+                                                                                  CapArgs cap) {
+    constexpr int NT = kPermSmallWaves * kWave;
+    constexpr int DSTR = kMaxRouterRows + 1;
+    __shared__ float dots[kRouterFusedT * DSTR];
+    __shared__ float prevs[kRouterFusedT * (kMaxExperts + 1)];
+    __shared__ float wres[kMaxExperts * kMaxExperts];
+    __shared__ float sbias[kMaxExperts];
+    __shared__ int s_idx[kRouterFusedT * kMaxTopK];
+    __shared__ int s_rank[kPermSmallWaves][kMaxExperts];
+    __shared__ int s_first[kMaxExperts], s_limit[kMaxExperts];
+    const int tid = threadIdx.x;
+    const int T = a.d.T, N = a.d.N, K = a.d.k, rows = N + 2 * a.d.n_const;
+    for (int c = tid; c < T * rows; c += NT) {
+        // element c = (token c / rows, row c % rows) of every slice; all loads first, then the sum in slice order
+        float v[kRsSplits];
+#pragma unroll
+        for (int sp = 0; sp < kRsSplits; ++sp) v[sp] = sp < n_splits ? partial[(size_t)sp * T * rows + c] : 0.f;
+        float sum = 0.f;
+#pragma unroll
+        for (int sp = 0; sp < kRsSplits; ++sp) sum += v[sp];
+        dots[(c / rows) * DSTR + c % rows] = sum;
+    }
+    if (a.prev_gate) {
+        for (int c = tid; c < T * N; c += NT) prevs[(c / N) * (kMaxExperts + 1) + c % N] = a.prev_gate[c];
+        for (int c = tid; c < N * N; c += NT) wres[c] = a.W_res[c];
+    }
+    if (tid < N) sbias[tid] = a.bias ? a.bias[tid] : 0.f;
+    __syncthreads();
+    for (int c = tid; c < T * N; c += NT) {
+        const int tt = c / N, i = c % N;
+        float L = dots[tt * DSTR + i];
+        if (a.prev_gate) {
+            const float *pr = prevs + tt * (kMaxExperts + 1);
+            const float *wr = wres + i * N;
+            float r = 0.f;
+            for (int m = 0; m < N; ++m) r = fmaf(wr[m], pr[m], r);
+            L += r;
+        }
+        L += sbias[i];
+        dots[tt * DSTR + i] = L;        // only this thread reads or writes the element
+        a.out_gate[c] = L;
+    }
+    __syncthreads();
+    {
+        // every thread runs this (the shuffles are wave-wide); threads past the last token
+        // compute on the last token and store nothing
+        const int tok = tid >> 2;
+        const int tk = tok < T ? tok : T - 1;
+        router_token_quad(a, (size_t)tk, tok < T, tid & 3, dots + tk * DSTR, nullptr, s_idx + tk * K);
+    }
+    __syncthreads();
+    perm_small_body(a.d, w, cap, s_idx, s_rank, s_first, s_limit);
+}
+
 size_t router_small_bytes() {
     return (size_t)kRsSplits * kRouterSmallT * kMaxRouterRows * sizeof(float);
 }
 
-hipError_t launch_router_small(const RouterArgs &a, bool bf16, float *partial, hipStream_t s) {
+hipError_t launch_router_small(const RouterArgs &a, bool bf16, float *partial, hipStream_t s,
+                               const Workspace *perm_ws, const CapArgs *perm_cap) {
     if (a.d.T == 0) return hipSuccess;
     if (a.d.T > kRouterSmallT) return hipErrorInvalidValue;
     const int tiles = (a.d.D + kRsBK - 1) / kRsBK;
@@ -230,6 +294,12 @@ hipError_t launch_router_small(const RouterArgs &a, bool bf16, float *partial, h
     if (rows <= 24) go(std::integral_constant<int, 6>());
     else if (rows <= 40) go(std::integral_constant<int, 10>());
     else go(std::integral_constant<int, 20>());
+    if (perm_ws) {
+        if (a.d.T > kRouterFusedT || perm_cap == nullptr) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(k_router_small_final_perm, dim3(1), dim3(kPermSmallWaves * kWave), 0, s, a, n_splits,
+                           partial, *perm_ws, *perm_cap);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(k_router_small_final, dim3((a.d.T + kRouterWaves - 1) / kRouterWaves),
                        dim3(kRouterWaves * kWave), 0, s, a, n_splits, partial);
     return hipGetLastError();

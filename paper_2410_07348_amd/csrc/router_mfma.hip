@@ -39,6 +39,7 @@
 // expert: its TOK * k slots are one chunk of the permutation that follows, which
 // then needs no histogram pass of its own.
 #include "common.h"
+#include "router_device.h"
 
 namespace moepp {
 
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int l32 = lane % 32, lh = lane / 32;
     const int tb = wave % TB, kh = wave / TB;             // token block, K-step parity
-    const int D = a.d.D, N = a.d.N, K = a.d.k, nc = a.d.n_const, T = a.d.T;
+    const int D = a.d.D, N = a.d.N, nc = a.d.n_const, T = a.d.T;
     const int rows = N + 2 * nc;
     const int t0 = blockIdx.x * kRtTok;
     const int KT = D / kRtBK;                             // a multiple of PF (the launcher checks)
@@ -279,54 +280,13 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
     }
     __syncthreads();
 
-    // Softmax, Top-K, a1: threads 4 tok .. 4 tok + 3 share token tok; thread q owns
-    // the experts i = q, q + 4, ...  (every thread runs this, so the shuffles are
-    // whole; tokens past the end compute on a copy of the last token and store nothing)
+    // Softmax, Top-K, a1: threads 4 tok .. 4 tok + 3 share token tok (every thread
+    // runs this, so the shuffles are whole; tokens past the end compute on a copy of
+    // the last token and store nothing)
     {
-        const int tok = tid >> 2, q = tid & 3;
-        const bool valid = tok < n_tok;
-        const float *Lr = dots + tok * DSTR;
-        float mx = -INFINITY;
-        for (int i = q; i < N; i += 4) mx = fmaxf(mx, Lr[i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 1, kWave));
-        mx = fmaxf(mx, __shfl_xor(mx, 2, kWave));
-        float sum = 0.f;
-        for (int i = q; i < N; i += 4) sum += __expf(Lr[i] - mx);
-        sum += __shfl_xor(sum, 1, kWave);
-        sum += __shfl_xor(sum, 2, kWave);
-        const float inv = 1.f / sum;
-        unsigned long long taken = 0ull;            // of this thread's own experts
-        const size_t t = (size_t)(t0 + tok);
-        for (int s = 0; s < K; ++s) {
-            float bv = -INFINITY;
-            int bi = 0x7fffffff;                    // none yet
-            for (int i = q; i < N; i += 4) {
-                const float v = Lr[i];
-                if (!((taken >> i) & 1ull) && (bi == 0x7fffffff || v > bv)) {
-                    bv = v;
-                    bi = i;
-                }
-            }
-#pragma unroll
-            for (int o = 1; o <= 2; o <<= 1) {
-                const float ov = __shfl_xor(bv, o, kWave);
-                const int oi = __shfl_xor(bi, o, kWave);
-                // larger logit wins, equal logits go to the lower index
-                if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) {
-                    bv = ov;
-                    bi = oi;
-                }
-            }
-            if ((bi & 3) == q) taken |= 1ull << bi;
-            if (valid && q == 0) {
-                a.topk_idx[t * K + s] = bi;
-                a.topk_w[t * K + s] = __expf(bv - mx) * inv;
-                if (a.chunk_hist) atomicAdd(&s_hist[bi], 1);   // integer counts: the same on every run
-            }
-        }
-        if (valid)
-            for (int j = q; j < nc; j += 4)
-                a.alpha1[t * nc + j] = 1.f / (1.f + expf(Lr[N + 2 * j + 1] - Lr[N + 2 * j]));
+        const int tok = tid >> 2;
+        router_token_quad(a, (size_t)(t0 + tok), tok < n_tok, tid & 3, dots + tok * DSTR,
+                          a.chunk_hist ? s_hist : nullptr, nullptr);
     }
     // out_gate block [n_tok, N] is contiguous in memory: coalesced copy from LDS
     for (int c = tid; c < n_tok * N; c += kRtThreads)

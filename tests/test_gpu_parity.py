@@ -213,6 +213,10 @@ def test_tiny_token_counts(kw):
 
 @pytest.mark.parametrize("act", ["bf16", "f32"])
 @pytest.mark.parametrize("kw", [
+    dict(T=1, seed=118),                         # one token
+    dict(T=64, seed=119),                        # last size at which the router's second kernel also permutes
+    dict(T=64, k=4, seed=120),                   # ... with four slots per token
+    dict(T=65, seed=121),                        # first size with a permutation launch of its own
     dict(T=256, seed=111),                       # last size of the few-token router
     dict(T=257, seed=112),                       # first size of the ordinary routers
     dict(T=2048, seed=113),                      # 4096 slots: last size of the one-workgroup permutation
@@ -232,6 +236,40 @@ def test_few_token_kernels_and_their_size_limits(kw, act):
     res = gpu_forward(s, inp, layer=L, cap=cap, balance_tau=0.75)
     errs = check_layer(s, inp, res, cap=np.array(cap, np.int32), balance_tau=0.75)
     say("  ", errs)
+
+
+def test_few_token_step_calls_with_capacities_set_after_the_routing():
+    """At a handful of tokens the routing call already groups the slots.  Capacities
+    set between moepp_route and moepp_permute must still take effect, a repeated
+    moepp_permute must change nothing, and the step calls must give what one
+    moepp_layer_forward call gives."""
+    import torch
+    s = small_shape("fewsteps", T=48, seed=131)
+    inp = make_inputs(s)
+    dev = to_device(s, inp)
+    L = make_layer(s)
+    cap = [max(1, c // 2) for c in L.capacity(s.T, 1.1, 0.75)]      # tight: assignments are dropped
+    ref = gpu_forward(s, inp, layer=L, dev=dev, cap=cap)             # capacities first, one call
+    assert int(ref["kept"].sum()) < s.T * s.k, "the capacities of this test must drop something"
+    check_layer(s, inp, ref, cap=np.array(cap, np.int32))
+    packed = L.pack_experts(dev["w1"], dev["w3"], dev["w2"])
+    L.set_capacity(None)
+    L.route(dev["x"], dev["prev_gate"], dev["W_g"], dev["W_res"], dev["W_c"])
+    torch.cuda.synchronize()
+    assert int(L.get_kept().sum().item()) == s.T * s.k               # grouped without capacities
+    L.set_capacity(cap)
+    for _ in range(2):
+        L.permute()
+        L.expert_ffn(dev["x"], packed)
+        out = L.combine(dev["x"], dev["const_vecs"])
+        torch.cuda.synchronize()
+        r = L.get_routing()
+        for key in ("counts", "offsets", "row_of"):
+            assert np.array_equal(r[key].cpu().numpy(), ref[key]), key
+        R = int(ref["offsets"][-1])
+        assert np.array_equal(r["src_of"].cpu().numpy()[:R], ref["src_of"][:R])
+        assert np.array_equal(L.get_kept().cpu().numpy(), ref["kept"])
+        assert np.array_equal(out.float().cpu().numpy().astype(np.float64), ref["out"])
 
 
 def test_zero_tokens_and_smaller_T_than_T_max():
