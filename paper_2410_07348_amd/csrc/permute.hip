@@ -3,11 +3,12 @@
 // exclusive scan over the chunks and a scatter give every slot its row.  The
 // histogram comes from the router kernel when that one counted its own
 // workgroup's selections (then a chunk is the slots of one router workgroup),
-// else from k_perm_hist; scan and scatter are one kernel in which every wave
-// adds up the histogram rows it needs itself (a few thousand chunks at most:
-// the rows are 4 N bytes each and sit in L2), or two kernels with a
-// single-workgroup scan when there are more chunks than that; calls with few
-// slots do all of it in one workgroup.  Integer work only and no ordering left
+// else from k_perm_hist; scan and scatter are one kernel in which every
+// workgroup adds up the histogram rows its waves need itself (a few thousand
+// chunks at most: the rows are 4 N bytes each and sit in L2), or two kernels
+// with a single-workgroup scan when there are more chunks than that; calls with
+// few slots do all of it in one workgroup (k_perm_small, or, with a handful of
+// tokens, the last kernel of the few-token router).  Integer work only and no ordering left
 // to atomics, so the result is the same on every run: rows of one expert are
 // ordered by ascending slot index q = t*k + s.
 //
