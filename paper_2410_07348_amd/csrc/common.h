@@ -113,6 +113,8 @@ struct RouterArgs {
     float *topk_w;
     float *alpha1;
     int32_t *chunk_hist;  // MFMA router: [workgroup][N] selections per expert, or null
+    double *bal_partial;  // MFMA router: [workgroup][kMaxExperts] sums of Softmax(G(x))_i over the
+                          // workgroup's tokens (for P_i of Eq.7), or null
 };
 
 struct FfnArgs {
@@ -164,9 +166,11 @@ hipError_t launch_perm_scan_scatter(const Dims &d, const Workspace &w, const Cap
 constexpr int kPermSmallWaves = 16;
 constexpr int kPermSmallSlots = kPermSmallWaves * kPermChunk;
 hipError_t launch_perm_small(const Dims &d, const Workspace &w, const CapArgs &cap, hipStream_t s);
-// f_i, P_i and L_b of Eq.7 from the logits of the routed call and the counts of the permutation
+// f_i, P_i and L_b of Eq.7 from the logits of the routed call and the counts of the permutation.
+// router_rows > 0: the router kernel has already left that many rows of per-workgroup sums of
+// Softmax(G(x)) in w.bal_partial (at most kBalWaves), and only the final reduction runs.
 hipError_t launch_balance(const Dims &d, const Workspace &w, const float *out_gate, float tau,
-                          hipStream_t s);
+                          hipStream_t s, int router_rows = 0);
 
 hipError_t launch_ffn_generic(const FfnArgs &a, bool bf16, int which, hipStream_t s);
 bool ffn_mfma_supported(const Dims &d);

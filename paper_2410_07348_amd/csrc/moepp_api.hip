@@ -24,6 +24,8 @@ struct moepp_ctx {
     const float *last_out_gate;   // logits of the last routed call (read by the statistics)
     int last_T, last_k;
     // the MFMA router leaves a histogram per workgroup for the permutation of the same call
+    int bal_rows;         // > 0: the router kernel of call (bal_T) left this many rows of Softmax sums
+    int bal_T;
     bool perm_valid;      // the few-token router kernel has already grouped the slots of call (perm_T, perm_k)
     int perm_T, perm_k;
     bool hist_valid;
@@ -182,6 +184,7 @@ moepp_status do_route(moepp_ctx *c, hipStream_t s, int T, const void *x, const f
     a.topk_w = c->ws.topk_w;
     a.alpha1 = c->ws.alpha1;
     a.chunk_hist = nullptr;
+    a.bal_partial = nullptr;
     moepp_status st = MOEPP_OK;
     const bool mfma = use_mfma_router(c, a.d, &st);
     if (st != MOEPP_OK) return st;
@@ -190,6 +193,7 @@ moepp_status do_route(moepp_ctx *c, hipStream_t s, int T, const void *x, const f
     c->last_out_gate = out_gate;
     c->hist_valid = false;
     c->perm_valid = false;
+    c->bal_rows = 0;
     if (T == 0) return MOEPP_OK;
     KernelTimer kt(c, s, MOEPP_K_ROUTER);
     const bool bf16 = c->desc.act == MOEPP_BF16;
@@ -210,6 +214,14 @@ moepp_status do_route(moepp_ctx *c, hipStream_t s, int T, const void *x, const f
             c->hist_T = T;
             c->hist_k = k;
             c->hist_chunk_slots = router_mfma_block_tokens(a.d) * k;
+        }
+        // with the load-balance statistics on, the kernel also adds up the softmax of its tokens
+        const int tok = router_mfma_block_tokens(a.d);
+        const int wgs = (T + tok - 1) / tok;
+        if (c->bal_tau > 0.0 && wgs <= kBalWaves) {
+            a.bal_partial = c->ws.bal_partial;
+            c->bal_rows = wgs;
+            c->bal_T = T;
         }
         e = launch_router_mfma(a, s);
     } else {
@@ -233,7 +245,8 @@ moepp_status do_permute(moepp_ctx *c, hipStream_t s, int T, int k) {
         if (e != hipSuccess) return MOEPP_EHIP;
         if (c->bal_tau > 0.0) {
             KernelTimer kt(c, s, MOEPP_K_BALANCE);
-            e = launch_balance(d, c->ws, c->last_out_gate, (float)c->bal_tau, s);
+            e = launch_balance(d, c->ws, c->last_out_gate, (float)c->bal_tau, s,
+                               c->bal_rows > 0 && c->bal_T == T ? c->bal_rows : 0);
         }
         return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
     }
@@ -261,7 +274,8 @@ moepp_status do_permute(moepp_ctx *c, hipStream_t s, int T, int k) {
     if (e != hipSuccess) return MOEPP_EHIP;
     if (c->bal_tau > 0.0 && T > 0) {
         KernelTimer kt(c, s, MOEPP_K_BALANCE);
-        e = launch_balance(d, c->ws, c->last_out_gate, (float)c->bal_tau, s);
+        e = launch_balance(d, c->ws, c->last_out_gate, (float)c->bal_tau, s,
+                           c->bal_rows > 0 && c->bal_T == T ? c->bal_rows : 0);
     }
     return e == hipSuccess ? MOEPP_OK : MOEPP_EHIP;
 }
@@ -386,6 +400,7 @@ void init_ctx(moepp_ctx *c, const moepp_desc *desc, void *workspace) {
     c->last_k = desc->k;
     c->hist_valid = false;
     c->perm_valid = false;
+    c->bal_rows = c->bal_T = 0;
     c->hist_T = c->hist_k = c->hist_chunk_slots = 0;
     c->timing = false;
     c->have_events = false;

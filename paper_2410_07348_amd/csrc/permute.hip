@@ -228,7 +228,8 @@ __global__ __launch_bounds__(kPermSmallWaves *kWave) void k_perm_small(Dims d, W
 // ---- load-balance statistics (Eq.7) ---------------------------------------
 // Pass 1: wave g takes tokens g, g + kBalWaves, ...; lane i owns expert i,
 // recomputes Softmax(G(x_t))_i from the logits the router wrote and adds it
-// up in fp64.  Pass 2: one workgroup adds the per-wave sums in a fixed order
+// up in fp64 (not needed when the matrix-core router has left the sums of its
+// workgroups' tokens itself).  Pass 2: one workgroup adds the per-wave sums in a fixed order
 // (the result is the same on every run), P_i = sum / T, f_i = counts_i / T,
 // L_b = sum_i eta_i f_i P_i with eta = 1 for FFN experts, tau for the others.
 __global__ __launch_bounds__(4 * kWave) void k_balance_partial(Dims d, Workspace w, const float *out_gate) {
@@ -245,13 +246,22 @@ __global__ __launch_bounds__(4 * kWave) void k_balance_partial(Dims d, Workspace
 }
 
 constexpr int kBalFinalWaves = 16;
-__global__ __launch_bounds__(kBalFinalWaves *kWave) void k_balance_final(Dims d, Workspace w, float tau) {
+__global__ __launch_bounds__(kBalFinalWaves *kWave) void k_balance_final(Dims d, Workspace w, float tau,
+                                                                        int n_rows) {
     __shared__ double part[kBalFinalWaves][kWave];
     const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
-    // wave wv adds its block of per-wave sums in index order, wave 0 the 16 block sums in order
-    constexpr int per = kBalWaves / kBalFinalWaves;
+    // wave wv adds its block of the n_rows partial sums in index order, wave 0 the 16 block sums in order
+    // (rows written by the router kernel hold nothing for lanes >= N: those lanes' sums are not used)
+    const int per = (n_rows + kBalFinalWaves - 1) / kBalFinalWaves;
     double sum = 0.0;
-    for (int g = wv * per; g < (wv + 1) * per; ++g) sum += w.bal_partial[(size_t)g * kMaxExperts + lane];
+    const int g_end = min((wv + 1) * per, n_rows);
+    for (int g0 = wv * per; g0 < g_end; g0 += 8) {         // eight loads in flight, added in index order
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = g0 + u < g_end ? w.bal_partial[(size_t)(g0 + u) * kMaxExperts + lane] : 0.0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += v[u];
+    }
     part[wv][lane] = sum;
     __syncthreads();
     if (wv != 0) return;
@@ -312,10 +322,13 @@ hipError_t launch_perm_small(const Dims &d, const Workspace &w, const CapArgs &c
     return hipGetLastError();
 }
 hipError_t launch_balance(const Dims &d, const Workspace &w, const float *out_gate, float tau,
-                          hipStream_t s) {
+                          hipStream_t s, int router_rows) {
     if (d.T == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_balance_partial, dim3(kBalWaves / 4), dim3(4 * kWave), 0, s, d, w, out_gate);
-    hipLaunchKernelGGL(k_balance_final, dim3(1), dim3(kBalFinalWaves * kWave), 0, s, d, w, tau);
+    if (router_rows > kBalWaves) return hipErrorInvalidValue;
+    if (router_rows <= 0)
+        hipLaunchKernelGGL(k_balance_partial, dim3(kBalWaves / 4), dim3(4 * kWave), 0, s, d, w, out_gate);
+    hipLaunchKernelGGL(k_balance_final, dim3(1), dim3(kBalFinalWaves * kWave), 0, s, d, w, tau,
+                       router_rows > 0 ? router_rows : kBalWaves);
     return hipGetLastError();
 }
 

@@ -12,8 +12,9 @@ namespace moepp {
 // (the shuffles are wave-wide); `valid` false: compute, store nothing.
 // hist (LDS, may be null): selections per expert, counted with integer atomics.
 // sel (LDS, may be null): sel[s] receives the expert of slot s.
+// probs (LDS, may be null): probs[i] receives Softmax(G(x))_i, 0 when not valid.
 __device__ inline void router_token_quad(const RouterArgs &a, size_t t, bool valid, int q, const float *Lr,
-                                         int *hist, int *sel) {
+                                         int *hist, int *sel, float *probs = nullptr) {
     const int N = a.d.N, K = a.d.k, nc = a.d.n_const;
     float mx = -INFINITY;
     for (int i = q; i < N; i += 4) mx = fmaxf(mx, Lr[i]);
@@ -56,6 +57,8 @@ __device__ inline void router_token_quad(const RouterArgs &a, size_t t, bool val
     if (valid)
         for (int j = q; j < nc; j += 4)
             a.alpha1[t * nc + j] = 1.f / (1.f + expf(Lr[N + 2 * j + 1] - Lr[N + 2 * j]));
+    if (probs)
+        for (int i = q; i < N; i += 4) probs[i] = valid ? __expf(Lr[i] - mx) * inv : 0.f;
 }
 
 }  // namespace moepp

@@ -285,15 +285,28 @@ __global__ __launch_bounds__(4 * TOK, WPE) void k_router_mfma(RouterArgs a) {
     // the last token and store nothing)
     {
         const int tok = tid >> 2;
+        // (prevs is free again: the probabilities of the load-balance statistics go there)
         router_token_quad(a, (size_t)(t0 + tok), tok < n_tok, tid & 3, dots + tok * DSTR,
-                          a.chunk_hist ? s_hist : nullptr, nullptr);
+                          a.chunk_hist ? s_hist : nullptr, nullptr,
+                          a.bal_partial ? prevs + tok * (N + 1) : nullptr);
     }
     // out_gate block [n_tok, N] is contiguous in memory: coalesced copy from LDS
     for (int c = tid; c < n_tok * N; c += kRtThreads)
         a.out_gate[(size_t)t0 * N + c] = dots[(c / N) * DSTR + c % N];
-    if (a.chunk_hist) {
-        __syncthreads();
+    if (a.chunk_hist || a.bal_partial) __syncthreads();
+    if (a.chunk_hist)
         for (int c = tid; c < N; c += kRtThreads) a.chunk_hist[(size_t)blockIdx.x * N + c] = s_hist[c];
+    if (a.bal_partial && tid < 4 * N) {
+        // sum of Softmax(G(x))_e over the workgroup's tokens (P_e of Eq.7 is the mean over all
+        // tokens): threads 4 e .. 4 e + 3 add a quarter of the tokens each, in token order, and
+        // the four sums are added as (0 + 1) + (2 + 3): the same on every run
+        const int e = tid >> 2, part = tid & 3;
+        double sum = 0.0;
+        for (int tt = part * (kRtTok / 4); tt < (part + 1) * (kRtTok / 4); ++tt)
+            sum += (double)prevs[tt * (N + 1) + e];
+        sum += __shfl_xor(sum, 1, kWave);
+        sum += __shfl_xor(sum, 2, kWave);
+        if (part == 0) a.bal_partial[(size_t)blockIdx.x * kMaxExperts + e] = sum;
     }
 }
 
