@@ -351,15 +351,18 @@ def test_step_calls_equal_the_fused_call_and_timing_reports():
 @pytest.mark.parametrize("variant", [1, 2])
 def test_more_chunks_than_one_scatter_kernel_scans_itself(variant):
     """So many slots that the permutation falls back to a scan kernel of its own
-    (more than 2048 chunks), with capacities on; with the MFMA router the chunks
-    are the router's 64-token workgroups, with the generic one 256 slots."""
+    (more than 2048 chunks), with capacities and load-balance statistics on; with
+    the MFMA router the chunks are the router's 64-token workgroups (more of them
+    than the statistics have rows for: the pass over the logits runs), with the
+    generic one 256 slots."""
     s = small_shape("manychunks", T=270000, D=128, F=64, n_ffn=5, seed=151)
     inp = make_inputs(s)
     L = make_layer(s)
     cap = L.capacity(s.T, 1.1, 0.75)
-    res = gpu_forward(s, inp, variant=variant, layer=L, cap=cap, intermediates=False)
+    res = gpu_forward(s, inp, variant=variant, layer=L, cap=cap, intermediates=False, balance_tau=0.75)
     toks = sample_tokens(s, res["topk_idx"], 2048, seed=3)
-    say("many chunks", check_layer(s, inp, res, tok_list=toks, cap=np.array(cap, np.int32), check_inter=False))
+    say("many chunks", check_layer(s, inp, res, tok_list=toks, cap=np.array(cap, np.int32), check_inter=False,
+                                   balance_tau=0.75))
 
 
 def test_step_calls_in_any_mix_leave_the_same_permutation():
