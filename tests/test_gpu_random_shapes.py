@@ -49,3 +49,37 @@ def test_random_shape_against_the_oracle(i):
         res = gpu_forward(s, inp, variant=variant, layer=L, cap=cap, balance_tau=tau)
         errs = check_layer(s, inp, res, cap=None if cap is None else np.array(cap, np.int32), balance_tau=tau)
         print("  variant", variant, errs, flush=True)
+
+
+def draw_medium(i):
+    rng = np.random.default_rng(9500 + i)
+    D = int(rng.choice([256, 512, 1024, 1536]))
+    F = int(rng.choice([256, 704, 1408]))
+    n_ffn = int(rng.choice([3, 8, 24]))
+    n_zero, n_copy = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+    n_const = int(rng.choice([0, 2, 6]))
+    k = int(rng.choice([1, 2, 2, 4]))
+    T = int(rng.choice([5000, 12000, 20000, 33000]))
+    return LayerShape("med%d" % i, T=T, D=D, F=F, n_ffn=n_ffn, n_zero=n_zero, n_copy=n_copy,
+                      n_const=n_const, k=min(k, n_ffn + n_zero + n_copy + n_const), act="bf16",
+                      residual=bool(rng.random() < 0.8),
+                      bias=str(rng.choice(["none", "normal"])), seed=7500 + i), bool(rng.random() < 0.5)
+
+
+@pytest.mark.parametrize("i", range(8))
+def test_random_medium_shape_against_the_oracle(i):
+    """Sizes at which the tiled GEMM runs several rounds of tiles and the permutation
+    has hundreds of chunks; routing and permutation on all tokens, outputs and
+    intermediates on a seeded sample of 1024 tokens that covers every selected expert."""
+    from helpers import sample_tokens
+    s, with_cap = draw_medium(i)
+    print("shape", s, "capacities", with_cap, flush=True)
+    inp = make_inputs(s)
+    L = make_layer(s)
+    cap = L.capacity(s.T, 1.1, 0.75) if with_cap else None
+    tau = 0.75 if with_cap else 0.0
+    res = gpu_forward(s, inp, variant=0, layer=L, cap=cap, balance_tau=tau)
+    toks = sample_tokens(s, res["topk_idx"], 1024, seed=11 + i)
+    errs = check_layer(s, inp, res, tok_list=toks, cap=None if cap is None else np.array(cap, np.int32),
+                       balance_tau=tau)
+    print("  ", errs, flush=True)
